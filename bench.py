@@ -1,0 +1,238 @@
+#!/usr/bin/env python3
+"""Benchmark of the MONA optimizer step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+One "step" is one mona_step over every matrix of the workload: the fused elementwise state
+kernel + norm, T = 5 Newton-Schulz iterations as grouped bf16 MFMA products, and the update
+fused into the last product.  Inputs (bf16 parameters, fp32 gradients from the seeded AR(1)
+generator) are resident in HBM before the timed region; a ring of gradient sets is cycled so
+that consecutive steps see different gradients.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_F32_MFMA_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def cpu_baseline(workload, hp, budget_s: float = 30.0):
+    """Time the float64 oracle (as it stands) on a bounded sample of the workload's matrices
+    and extrapolate to a whole step by the flop count of the oracle's literal formulation."""
+    import numpy as np
+    import torch
+
+    from oracle import mona_oracle as orc
+    from paper_2605_26842_amd import workloads as wl
+
+    ohp = orc.OracleHParams(hp.lr, hp.momentum, hp.beta_a, hp.alpha, hp.weight_decay, hp.ns_steps,
+                            hp.ns_a, hp.ns_b, hp.ns_c, hp.ns_eps, hp.gamma_coeff).f32()
+
+    def literal_flops(m, n):
+        # S = X X^T (m x m), S X, S (S X): 3 products of 2 m^2 n flop per iteration
+        return ohp.ns_steps * 3 * 2.0 * m * m * n + 20.0 * m * n
+
+    shapes = workload.shapes()
+    classes = {}
+    for s in shapes:
+        classes[s] = classes.get(s, 0) + 1
+    # cheapest classes first; stop when the budget is used
+    order = sorted(classes, key=lambda s: literal_flops(*s))
+    measured, spent = {}, 0.0
+    rate = None  # flop/s seen so far
+    for s in order:
+        est = literal_flops(*s) / rate if rate else 0.0
+        if measured and spent + est > budget_s:
+            continue
+        w = wl.draw_weight(s, 123, torch.float32).double().numpy()
+        g = wl.GradientStream(s, 456).next().double().numpy()
+        o = orc.MonaOracle(s)
+        t0 = time.perf_counter()
+        o.step(w, g, ohp)
+        dt = time.perf_counter() - t0
+        measured[s] = dt
+        spent += dt
+        rate = literal_flops(*s) / dt
+    total = 0.0
+    for s, cnt in classes.items():
+        if s in measured:
+            total += cnt * measured[s]
+        else:
+            total += cnt * literal_flops(*s) / rate
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    return {
+        "value": 1.0 / total, "unit": "steps/s", "cores": int(threads), "kind": "oracle",
+        "sample": ("one float64 oracle step on one matrix of each of the shape classes "
+                   f"{sorted(measured)} ({spent:.1f} s measured), whole-workload time "
+                   f"({total:.1f} s/step) extrapolated by matrix count and, for unmeasured classes, by flop count"),
+        "seconds_per_step_extrapolated": total,
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="moe_layer_h4096_e128")
+    ap.add_argument("--ns-precision", type=int, default=0)
+    ap.add_argument("--state-dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--g-dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--grad-ring", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--per-launch", action="store_true", help="also print per-launch timings to stderr")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    from paper_2605_26842_amd import binding as B
+    from paper_2605_26842_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    workload = wl.WORKLOADS[args.workload]
+    widx = list(wl.WORKLOADS).index(args.workload)
+    hp = wl.HParams()
+    shapes = workload.shapes()
+    g_dtype = torch.float32 if args.g_dtype == "f32" else torch.bfloat16
+    state_dtype = torch.float32 if args.state_dtype == "f32" else torch.bfloat16
+
+    # inputs, resident before timing
+    weights = [wl.draw_weight(s, wl.matrix_seed(widx, i), workload.w_dtype, dev) for i, s in enumerate(shapes)]
+    ring = []
+    streams = None
+    for r in range(max(1, args.grad_ring)):
+        if streams is None:
+            # one generator state per shape class keeps the host loop short; each matrix still
+            # gets its own draw
+            streams = [wl.GradientStream(s, wl.matrix_seed(widx, i), dev) for i, s in enumerate(shapes)]
+        ring.append([st.next().to(g_dtype) for st in streams])
+    del streams
+    opt = B.MonaOptimizer(weights, ns_precision=args.ns_precision, state_dtype=state_dtype, g_dtype=g_dtype)
+    hpc = B.make_hparams(hp)
+    plan = opt.plan_info(hp.ns_steps)
+    torch.cuda.synchronize()
+
+    k = 0
+    for _ in range(args.warmup):
+        opt.step(ring[k % len(ring)], hpc)
+        k += 1
+    torch.cuda.synchronize()
+
+    # timed region: exactly --steps steps; phase times come from HIP events that mona_step
+    # records on the stream it launches on
+    opt.set_profiling(1)
+    phase = [0.0, 0.0, 0.0, 0.0]
+    n_phase = 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        opt.step(ring[k % len(ring)], hpc)
+        k += 1
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    # events of the last timed step (the library keeps one set); then a few more profiled steps
+    # outside the timed region to average the phase split
+    times = opt.last_step_times()
+    phase = [phase[i] + times[i] for i in range(4)]
+    n_phase += 1
+    extra = min(args.steps, 5)
+    for _ in range(extra):
+        opt.step(ring[k % len(ring)], hpc)
+        k += 1
+        times = opt.last_step_times()
+        phase = [phase[i] + times[i] for i in range(4)]
+        n_phase += 1
+    ew_ms, ns_ms, upd_ms, step_ms_events = [p / n_phase for p in phase]
+
+    launches = None
+    if args.per_launch:
+        opt.set_profiling(2)
+        opt.step(ring[k % len(ring)], hpc)
+        k += 1
+        launches = opt.last_step_launches()
+        kinds = {0: "gram", 1: "poly", 2: "apply"}
+        for r in launches:
+            tf = r["flops"] / (r["ms"] * 1e-3) / 1e12 if r["ms"] > 0 else 0.0
+            print(f"[launch] {kinds[r['kind']]:5s} {r['m']}x{r['n']} x{r['count']} iter {r['iter']} tile {r['tile']}: "
+                  f"{r['ms']:.3f} ms  {tf:.1f} TFLOP/s issued", file=sys.stderr)
+        opt.set_profiling(1)
+
+    n_elem = workload.num_elements()
+    flops_sym = workload.ns_flops_symmetric(hp.ns_steps)
+    flops_dense = workload.ns_flops_dense(hp.ns_steps)
+    peak = PEAK_F32_MFMA_TFLOPS if args.ns_precision == 1 else PEAK_BF16_TFLOPS
+    ns_tflops = flops_sym / (ns_ms * 1e-3) / 1e12 if ns_ms > 0 else 0.0
+    ew_bytes = plan["elementwise_bytes"]
+    ew_gbs = ew_bytes / (ew_ms * 1e-3) / 1e9 if ew_ms > 0 else 0.0
+
+    out = {
+        "metric": "MONA optimizer steps/s",
+        "value": 1e3 / ms_per_step,
+        "unit": "steps/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if args.ns_precision == 0 else "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": args.workload, "matrices": len(shapes), "elements": n_elem,
+            "param_dtype": str(workload.w_dtype).replace("torch.", ""), "grad_dtype": args.g_dtype,
+            "state_dtype": args.state_dtype, "ns_steps": hp.ns_steps, "ns_precision": args.ns_precision,
+            "grad_ring": len(ring),
+        },
+        "roofline": {
+            "kernel": "ns_gemm (grouped Newton-Schulz products, %d launches/step)" % plan["ns_launches"],
+            "bound": "mfma", "achieved": ns_tflops, "peak": peak, "unit": "TFLOP/s",
+            "frac": ns_tflops / peak,
+            "traffic": None,
+            "flops_per_step_algorithmic": flops_sym,
+            "flops_per_step_issued": plan["ns_flops_issued"],
+            "flops_per_step_dense_equivalent": flops_dense,
+            "ms_per_step": ns_ms,
+            "avg_launch_ms": ns_ms / max(plan["ns_launches"], 1),
+        },
+        "elementwise": {
+            "kernel": "state_update + norm_finalize", "bound": "hbm", "achieved": ew_gbs, "peak": PEAK_HBM_GBS,
+            "unit": "GB/s", "frac": ew_gbs / PEAK_HBM_GBS, "bytes_per_step": ew_bytes, "ms_per_step": ew_ms,
+        },
+        "phases_ms": {"elementwise": ew_ms, "newton_schulz": ns_ms, "separate_update": upd_ms,
+                      "step_events": step_ms_events},
+        "ns_tflops_dense_equivalent": flops_dense / (ns_ms * 1e-3) / 1e12 if ns_ms > 0 else 0.0,
+        "ns_tflops_issued": plan["ns_flops_issued"] / (ns_ms * 1e-3) / 1e12 if ns_ms > 0 else 0.0,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(workload, hp)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

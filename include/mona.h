@@ -1,0 +1,196 @@
+/*
+ * libmona -- the MONA optimizer step (Muon with an acceleration term built from
+ * an EMA of gradient differences) for lists of weight matrices on one AMD
+ * MI355X (gfx950) GPU.
+ *
+ * What one step computes, per matrix W (m x n), in the order of the paper's
+ * Algorithm 1:
+ *
+ *     D_k   = G_k - G_{k-1}                          Alg. 1, difference line (Eq. alto_diff)
+ *     A_k   = beta_a A_{k-1} + (1 - beta_a) D_k      Eq. alto_accel
+ *     Gt_k  = G_k + alpha A_k                        Eq. alto_grad
+ *     M_k   = mu M_{k-1} + Gt_k                      Eq. muon_momentum, fed with Gt_k
+ *     X_0   = M_k / (||M_k||_F + eps)                Sec. 3.2, start of the Newton-Schulz iteration
+ *     X_t+1 = a X_t + b (X_t X_t^T) X_t + c (X_t X_t^T)^2 X_t,   t = 0..T-1     Eq. newton_schulz
+ *     O_k   = X_T
+ *     W_k+1 = W_k - eta (gamma O_k + lambda W_k),  gamma = gamma_coeff sqrt(max(m, n))    Eq. muon_update
+ *     G_{k-1} <- G_k                                 Alg. 1, last line of the loop
+ *
+ * with M_0 = A_0 = G_0 = 0 (Alg. 1, initialisation line).
+ *
+ * Conventions
+ *   - plain C ABI; every pointer argument says whether it is HOST or DEVICE memory;
+ *   - every function returns MONA_OK (0) or a negative mona_status and never throws;
+ *     mona_last_error() gives a thread-local description of the last failure;
+ *   - nothing here synchronises the stream unless stated; work is enqueued on the
+ *     stream the caller passes (a hipStream_t cast to void*, NULL = the null stream);
+ *   - the library allocates no device memory for state or workspace: the caller hands
+ *     it one arena (e.g. a torch uint8 tensor) sized by mona_state_size(); the library
+ *     owns only host-side bookkeeping and a few small pinned host tables.
+ */
+#ifndef MONA_H
+#define MONA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum mona_status {
+  MONA_OK = 0,
+  MONA_EINVAL = -1,       /* null pointer, size < 1, hyper-parameter out of range, misaligned pointer */
+  MONA_ESHAPE = -2,       /* matrix list differs from the one given to mona_init_state            */
+  MONA_ENOMEM = -3,       /* arena too small / host allocation failed                              */
+  MONA_EHIP = -4,         /* a HIP runtime call failed (text in mona_last_error)                   */
+  MONA_EUNSUPPORTED = -5  /* valid request this build does not implement                           */
+} mona_status;
+
+typedef enum mona_dtype { MONA_F32 = 0, MONA_BF16 = 1 } mona_dtype;
+
+/* One weight matrix.  The caller owns w and g (DEVICE memory, row-major, contiguous,
+ * m rows of n elements, 16-byte aligned).  w is updated in place (round-to-nearest-even
+ * when bf16); g is only read. */
+typedef struct mona_matrix {
+  void* w;            /* DEVICE: W_k in, W_{k+1} out                    */
+  const void* g;      /* DEVICE: G_k                                    */
+  int32_t m, n;       /* >= 1; m * n < 2^31                             */
+  int32_t w_dtype;    /* mona_dtype                                     */
+  int32_t g_dtype;    /* mona_dtype                                     */
+} mona_matrix;
+
+/* Alg. 1, REQUIRE line.  Passed per step because schedules change eta. */
+typedef struct mona_hparams {
+  float lr;            /* eta                                                            */
+  float momentum;      /* mu in [0, 1)                                                   */
+  float beta_a;        /* acceleration EMA coefficient in [0, 1)                         */
+  float alpha;         /* acceleration coefficient; 0 gives plain Muon (Sec. 3.2)        */
+  float weight_decay;  /* lambda, decoupled, acts on W_k, scaled by eta                  */
+  int32_t ns_steps;    /* T >= 0 (5 in the paper); 0 gives O = X_0                       */
+  float ns_a, ns_b, ns_c; /* 3.4445, -4.7750, 2.0315 (text under Eq. newton_schulz)      */
+  float ns_eps;        /* X_0 = M / (||M||_F + ns_eps); the paper uses 0                 */
+  float gamma_coeff;   /* 0.2 in gamma = 0.2 sqrt(max(m, n))                             */
+  uint32_t flags;      /* MONA_FLAG_* bits                                               */
+} mona_hparams;
+
+/* At the first step after mona_init_state take D_1 = 0 instead of D_1 = G_1 - 0, i.e.
+ * behave as if the previous-gradient buffer already held G_1.  Off by default
+ * (Alg. 1 initialises G_0 = 0). */
+#define MONA_FLAG_FIRST_DIFF_ZERO 0x1u
+/* Keep O_k = X_T readable through mona_state_view(MONA_VIEW_O) after the step (costs one
+ * extra store of the matrix in the update kernel). */
+#define MONA_FLAG_KEEP_O 0x2u
+
+/* Fixed when the state is built. */
+typedef struct mona_options {
+  int32_t ns_precision; /* 0: bf16 operands, fp32 accumulation (MFMA bf16);
+                           1: fp32 operands and accumulation (MFMA fp32)                     */
+  int32_t state_dtype;  /* mona_dtype of the stored G_{k-1} and A_k: MONA_F32 (Sec. 6.3,
+                           "full precision") or MONA_BF16 (the MONA-Lite variant, Sec. 6.3);
+                           M_k is always fp32                                                */
+  int32_t reserved[6];  /* must be 0 */
+} mona_options;
+
+typedef struct mona_state mona_state;   /* opaque, HOST */
+
+/* Bytes of DEVICE arena needed for `count` matrices (shapes and dtypes are read from
+ * mats; the w/g pointers are ignored and may be NULL).  Host-only: touches no GPU.
+ *   mats  HOST  array of count descriptors        opts  HOST (NULL = all zero)
+ *   bytes_out HOST                                                              */
+int mona_state_size(const mona_matrix* mats, int32_t count, const mona_options* opts,
+                    size_t* bytes_out);
+
+/* Alg. 1, initialisation line: lay the state {G_{k-1}, A, M} of every matrix and the
+ * Newton-Schulz workspace out in `arena`, zero it (on `stream`, which is synchronised once
+ * before returning), set k = 0 and build the launch plan (same-shape matrices are grouped
+ * and orthogonalised together).
+ *   arena  DEVICE, 256-byte aligned, arena_bytes >= mona_state_size(); stays the caller's
+ *          and must outlive the state
+ *   out    HOST   receives the handle; release with mona_free_state                  */
+int mona_init_state(const mona_matrix* mats, int32_t count, const mona_options* opts,
+                    void* arena, size_t arena_bytes, void* stream, mona_state** out);
+
+/* Alg. 1, one pass of the loop body for every matrix: enqueues the kernels on `stream`
+ * and returns without waiting.  `mats` must list the same shapes and dtypes, in the same
+ * order, as at init (else MONA_ESHAPE); w and g pointers may differ from step to step.
+ * Successive steps on one state must be issued on the same stream or be ordered by the
+ * caller. */
+int mona_step(mona_state* st, const mona_matrix* mats, int32_t count,
+              const mona_hparams* hp, void* stream);
+
+/* Release host bookkeeping (waits for the state's pinned tables to be idle).  The arena
+ * is not touched. */
+int mona_free_state(mona_state* st);
+
+typedef enum mona_view_kind {
+  MONA_VIEW_G_PREV = 0,  /* G_{k-1}: m x n, state dtype                                */
+  MONA_VIEW_A = 1,       /* A_k:     m x n, state dtype                                */
+  MONA_VIEW_M = 2,       /* M_k:     m x n, fp32                                       */
+  MONA_VIEW_NORM = 3,    /* ||M_k||_F of the last step: 1 x 1 fp32                      */
+  MONA_VIEW_O = 4        /* O_k of the last step (needs MONA_FLAG_KEEP_O): m x n with a
+                            leading dimension ld >= n, bf16 (ns_precision 0) or fp32 (1) */
+} mona_view_kind;
+
+typedef struct mona_view {
+  void* ptr;             /* DEVICE, inside the arena                                    */
+  int32_t rows, cols;
+  int32_t ld;            /* elements between consecutive rows                           */
+  int32_t dtype;         /* mona_dtype                                                  */
+} mona_view;
+
+/* Where a piece of matrix i's state lives (test and checkpoint hook).  The caller may
+ * read it, or write it between steps, after synchronising the stream. */
+int mona_state_view(mona_state* st, int32_t i, int32_t kind, mona_view* out);
+
+/* Checkpointing.  The persistent state is one contiguous block of the arena holding
+ * {G_{k-1}, A, M} of every matrix; export copies it to dst, import copies it back
+ * (both DEVICE-to-DEVICE, asynchronous on `stream`), and the step counter travels
+ * separately.  A state imported into a fresh mona_init_state of the same matrix list
+ * continues bit-identically. */
+int mona_state_export_size(mona_state* st, size_t* bytes_out);
+int mona_state_export(mona_state* st, void* dst, size_t dst_bytes, void* stream);
+int mona_state_import(mona_state* st, const void* src, size_t src_bytes, int64_t step_count,
+                      void* stream);
+int mona_state_step_count(mona_state* st, int64_t* k_out);
+
+/* Per-matrix status bits of the last step, copied to HOST after synchronising `stream`:
+ * bit 0: ||M||_F + eps == 0 (O = 0, only weight decay applied);
+ * bit 1: ||M||_F not finite (the matrix's W was left unchanged). */
+#define MONA_STATUS_ZERO_NORM 0x1u
+#define MONA_STATUS_NONFINITE 0x2u
+int mona_state_status(mona_state* st, uint32_t* host_out, int32_t count, void* stream);
+
+/* Elapsed GPU time of the phases of the last mona_step, from HIP events recorded on the
+ * stream the step ran on.  Enabled with mona_set_profiling(st, 1); waits for the step.
+ *   ms_out HOST float[4]: elementwise state + norm, Newton-Schulz products,
+ *                         update (0 when fused into the last product), whole step. */
+int mona_set_profiling(mona_state* st, int32_t level /* 0 off, 1 phases, 2 every launch */);
+int mona_last_step_times(mona_state* st, float* ms_out);
+
+/* With mona_set_profiling(st, 2) every Newton-Schulz product launch of a step is bracketed
+ * by its own pair of events.  mona_last_step_launches waits for the step and fills up to
+ * max_records entries (out may be NULL to query the count).
+ *   kind: 0 = Gram (X X^T), 1 = poly (b S + c S S), 2 = apply (a X + B X)
+ *   flops: MFMA flop the launch issues (tiles x 2 x tile^2 x K), padding included      */
+typedef struct mona_launch_time {
+  int32_t kind, group, iter, tile;
+  int32_t m, n, count;   /* shape of the group's matrices and how many there are */
+  float ms;
+  double flops;
+} mona_launch_time;
+int mona_last_step_launches(mona_state* st, mona_launch_time* out, int32_t max_records,
+                            int32_t* n_out);
+
+/* Number of kernel launches and executed MFMA flop of the Newton-Schulz part of one
+ * step under the current plan (host-only bookkeeping, for roofline reporting). */
+int mona_plan_info(mona_state* st, int32_t ns_steps, int64_t* launches_out,
+                   double* ns_flops_executed_out, double* elementwise_bytes_out);
+
+const char* mona_last_error(void);
+const char* mona_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MONA_H */

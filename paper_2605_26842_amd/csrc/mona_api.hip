@@ -1,0 +1,711 @@
+// Host side of libmona: argument checking, arena layout, shape grouping and the launch plan
+// of one MONA step (Alg. 1).  All arithmetic happens in the kernels of state_update.hip and
+// ns_gemm.hip; this file only decides what is launched on which buffers.
+#include "../../include/mona.h"
+#include "mona_internal.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace mona;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                       \
+  do {                                                                                      \
+    hipError_t e__ = (expr);                                                                \
+    if (e__ != hipSuccess) return fail(MONA_EHIP, "%s: %s", #expr, hipGetErrorString(e__)); \
+  } while (0)
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a; }
+int round_up(int v, int a) { return (v + a - 1) / a * a; }
+
+enum OpKind { OP_GRAM = 0, OP_POLY = 1, OP_APPLY = 2 };
+
+struct Group {
+  int m = 0, n = 0;          // native shape
+  bool tall = false;         // m > n: Gram matrix on the column side
+  int rows_pad = 0, cols_pad = 0;  // padded native shape of the working copies
+  int p_pad = 0;             // padded short side
+  int gran = 128;            // padding granularity (largest tile usable)
+  std::vector<int> members;  // matrix indices
+  size_t x_off[2] = {0, 0};  // byte offsets in the arena: ping-pong X buffers
+  size_t s_off = 0, b_off = 0;
+  size_t members_off = 0;
+  int64_t x_stride = 0, s_stride = 0;  // elements per matrix
+};
+
+struct Layout {
+  int count = 0;
+  int esize = 2;             // bytes per element of the Newton-Schulz working precision
+  int ssize = 4;             // bytes per element of the stored G_{k-1}, A
+  std::vector<size_t> gprev_off, acc_off, mom_off;
+  size_t state_begin = 0, state_bytes = 0;     // persistent {G_prev, A, M}
+  size_t work_begin = 0, work_bytes = 0;       // X, S, B of every group (zeroed once)
+  size_t stat_off = 0, dyn_off = 0, scales_off = 0, partials_off = 0, blocks_off = 0, optr_off = 0;
+  size_t total = 0;
+  std::vector<Group> groups;
+  std::vector<int> group_of, rank_in_group;
+  std::vector<BlockWork> blocks;       // ordered: fp32-gradient matrices first, then bf16
+  std::vector<int> first_block, num_blocks;
+  int blocks_f32g = 0;                 // number of leading blocks whose gradient is fp32
+};
+
+int check_mats(const mona_matrix* mats, int32_t count, bool need_ptrs) {
+  if (!mats) return fail(MONA_EINVAL, "mats is NULL");
+  if (count < 1) return fail(MONA_EINVAL, "count must be >= 1 (got %d)", count);
+  for (int i = 0; i < count; ++i) {
+    const mona_matrix& q = mats[i];
+    if (q.m < 1 || q.n < 1) return fail(MONA_EINVAL, "matrix %d: m and n must be >= 1 (got %d x %d)", i, q.m, q.n);
+    if ((int64_t)q.m * q.n >= (int64_t)1 << 31)
+      return fail(MONA_EINVAL, "matrix %d: m * n must be below 2^31 (got %d x %d)", i, q.m, q.n);
+    if ((q.w_dtype != MONA_F32 && q.w_dtype != MONA_BF16) || (q.g_dtype != MONA_F32 && q.g_dtype != MONA_BF16))
+      return fail(MONA_EINVAL, "matrix %d: dtype must be MONA_F32 or MONA_BF16", i);
+    if (need_ptrs) {
+      if (!q.w || !q.g) return fail(MONA_EINVAL, "matrix %d: w and g must not be NULL", i);
+      if (((uintptr_t)q.w & 15) || ((uintptr_t)q.g & 15))
+        return fail(MONA_EINVAL, "matrix %d: w and g must be 16-byte aligned", i);
+    }
+  }
+  return MONA_OK;
+}
+
+int check_opts(const mona_options* o, mona_options* out) {
+  mona_options z;
+  memset(&z, 0, sizeof z);
+  if (o) z = *o;
+  if (z.ns_precision != 0 && z.ns_precision != 1) return fail(MONA_EINVAL, "ns_precision must be 0 or 1");
+  if (z.state_dtype != MONA_F32 && z.state_dtype != MONA_BF16)
+    return fail(MONA_EINVAL, "state_dtype must be MONA_F32 or MONA_BF16");
+  for (int r : z.reserved)
+    if (r != 0) return fail(MONA_EINVAL, "reserved option fields must be 0");
+  *out = z;
+  return MONA_OK;
+}
+
+void build_layout(const mona_matrix* mats, int count, const mona_options& opt, Layout& L) {
+  L.count = count;
+  L.esize = opt.ns_precision == 1 ? 4 : 2;
+  L.ssize = opt.state_dtype == MONA_BF16 ? 2 : 4;
+  size_t off = 0;
+  // persistent state, contiguous: this block is what checkpoints carry
+  L.state_begin = off;
+  L.gprev_off.resize(count);
+  L.acc_off.resize(count);
+  L.mom_off.resize(count);
+  for (int i = 0; i < count; ++i) {
+    const size_t ne = (size_t)mats[i].m * mats[i].n;
+    L.gprev_off[i] = off; off = align_up(off + ne * L.ssize);
+    L.acc_off[i] = off;   off = align_up(off + ne * L.ssize);
+    L.mom_off[i] = off;   off = align_up(off + ne * 4);
+  }
+  L.state_bytes = off - L.state_begin;
+
+  // groups of equal shape (order of first appearance)
+  std::map<std::pair<int, int>, int> index;
+  L.group_of.resize(count);
+  L.rank_in_group.resize(count);
+  for (int i = 0; i < count; ++i) {
+    auto key = std::make_pair(mats[i].m, mats[i].n);
+    auto it = index.find(key);
+    int gi;
+    if (it == index.end()) {
+      gi = (int)L.groups.size();
+      index[key] = gi;
+      Group g;
+      g.m = mats[i].m;
+      g.n = mats[i].n;
+      g.tall = g.m > g.n;
+      const int r128 = round_up(g.m, 128), c128 = round_up(g.n, 128);
+      g.gran = (opt.ns_precision == 0 && r128 % 256 == 0 && c128 % 256 == 0) ? 256 : 128;
+      g.rows_pad = r128;
+      g.cols_pad = c128;
+      g.p_pad = g.tall ? g.cols_pad : g.rows_pad;
+      L.groups.push_back(g);
+    } else {
+      gi = it->second;
+    }
+    L.group_of[i] = gi;
+    L.rank_in_group[i] = (int)L.groups[gi].members.size();
+    L.groups[gi].members.push_back(i);
+  }
+  L.work_begin = off;
+  for (Group& g : L.groups) {
+    const size_t cnt = g.members.size();
+    g.x_stride = (int64_t)g.rows_pad * g.cols_pad;
+    g.s_stride = (int64_t)g.p_pad * g.p_pad;
+    for (int b = 0; b < 2; ++b) { g.x_off[b] = off; off = align_up(off + cnt * g.x_stride * L.esize); }
+    g.s_off = off; off = align_up(off + cnt * g.s_stride * L.esize);
+    g.b_off = off; off = align_up(off + cnt * g.s_stride * L.esize);
+  }
+  L.work_bytes = off - L.work_begin;
+
+  // elementwise work table
+  L.first_block.assign(count, 0);
+  L.num_blocks.assign(count, 0);
+  for (int pass = 0; pass < 2; ++pass) {
+    for (int i = 0; i < count; ++i) {
+      if ((mats[i].g_dtype == MONA_BF16) != (pass == 1)) continue;
+      const int64_t ne = (int64_t)mats[i].m * mats[i].n;
+      const int nb = (int)((ne + kEwChunk - 1) / kEwChunk);
+      L.first_block[i] = (int)L.blocks.size();
+      L.num_blocks[i] = nb;
+      for (int c = 0; c < nb; ++c) L.blocks.push_back(BlockWork{i, c});
+    }
+    if (pass == 0) L.blocks_f32g = (int)L.blocks.size();
+  }
+
+  // tables
+  L.stat_off = off;     off = align_up(off + sizeof(MatStatic) * count);
+  L.dyn_off = off;      off = align_up(off + sizeof(MatDynamic) * count);
+  L.scales_off = off;   off = align_up(off + sizeof(MatScale) * count);
+  L.optr_off = off;     off = align_up(off + sizeof(void*) * count);
+  L.partials_off = off; off = align_up(off + sizeof(float) * L.blocks.size());
+  L.blocks_off = off;   off = align_up(off + sizeof(BlockWork) * L.blocks.size());
+  for (Group& g : L.groups) { g.members_off = off; off = align_up(off + sizeof(int32_t) * g.members.size()); }
+  L.total = off;
+}
+
+constexpr int kRing = 4;
+
+struct LaunchRecord {
+  int kind, group, iter, tile;
+  double flops;
+  hipEvent_t e0, e1;
+};
+
+}  // namespace
+
+struct mona_state {
+  Layout L;
+  mona_options opt;
+  std::vector<mona_matrix> mats;   // shapes/dtypes given at init (pointers unused)
+  char* arena = nullptr;
+  int64_t k = 0;
+  // pinned ring for the per-step pointer table
+  MatDynamic* ring[kRing] = {nullptr, nullptr, nullptr, nullptr};
+  hipEvent_t ring_ev[kRing];
+  bool ring_used[kRing] = {false, false, false, false};
+  int ring_next = 0;
+  std::vector<MatDynamic> last_dyn;
+  bool dyn_valid = false;
+  int device = 0;
+  // profiling
+  int profiling = 0;
+  hipEvent_t ev[4];
+  bool ev_valid = false;
+  bool times_ready = false;
+  bool fused_update = false;
+  int o_buf = 1;                   // which ping-pong buffer holds O_k of the last step
+  std::vector<LaunchRecord> records;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> event_pool;
+  size_t pool_used = 0;
+
+  template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(arena + off); }
+};
+
+namespace {
+
+// tile used by one product of a group
+int pick_tile(const Group& g, int kind, int count, bool f32) {
+  if (f32 || g.gran < 256) return 128;
+  long long tiles;
+  if (kind == OP_APPLY) {
+    tiles = (long long)(g.rows_pad / 256) * (g.cols_pad / 256) * count;
+  } else {
+    const long long t = g.p_pad / 256;
+    tiles = t * (t + 1) / 2 * count;
+  }
+  return tiles >= 192 ? 256 : 128;
+}
+
+double gemm_flops(const GemmArgs& a, int tile) {
+  return 2.0 * tile * tile * (double)a.K * a.tiles_per_mat * a.count;
+}
+
+void fill_gemm(const mona_state* st, const Group& g, int kind, int tile, int src, const mona_hparams& hp, bool first,
+               bool last, GemmArgs& a, bool& tp, bool& tq) {
+  const Layout& L = st->L;
+  memset(&a, 0, sizeof a);
+  const int cnt = (int)g.members.size();
+  char* base = st->arena;
+  void* X = base + g.x_off[src];
+  void* Xn = base + g.x_off[src ^ 1];
+  void* S = base + g.s_off;
+  void* B = base + g.b_off;
+  a.count = cnt;
+  a.members = reinterpret_cast<const int32_t*>(base + g.members_off);
+  a.scales = st->at<MatScale>(L.scales_off);
+  a.stat = st->at<MatStatic>(L.stat_off);
+  a.dyn = st->at<MatDynamic>(L.dyn_off);
+  a.epilogue = EPI_STORE;
+  a.post = POST_NONE;
+  if (kind == OP_GRAM) {
+    a.P = X; a.Q = X; a.E = nullptr; a.C = S;
+    a.strideP = a.strideQ = g.x_stride; a.strideC = g.s_stride;
+    a.ldp = a.ldq = g.cols_pad; a.ldc = g.p_pad;
+    a.M = a.N = g.p_pad;
+    a.K = g.tall ? g.rows_pad : g.cols_pad;
+    tp = tq = g.tall;
+    a.symmetric = 1;
+    a.alpha = 1.0f; a.beta = 0.0f;
+    if (first) a.post = POST_INV2;
+  } else if (kind == OP_POLY) {
+    a.P = S; a.Q = S; a.E = S; a.C = B;
+    a.strideP = a.strideQ = a.strideE = a.strideC = g.s_stride;
+    a.ldp = a.ldq = a.lde = a.ldc = g.p_pad;
+    a.M = a.N = a.K = g.p_pad;
+    tp = tq = false;
+    a.symmetric = 1;
+    a.alpha = hp.ns_c; a.beta = hp.ns_b;
+  } else {
+    a.E = X; a.C = Xn;
+    a.strideE = a.strideC = g.x_stride;
+    a.lde = a.ldc = g.cols_pad;
+    a.K = g.p_pad;
+    a.M = g.rows_pad; a.N = g.cols_pad;
+    if (g.tall) {          // X' = a X + X B
+      a.P = X; a.strideP = g.x_stride; a.ldp = g.cols_pad;
+      a.Q = B; a.strideQ = g.s_stride; a.ldq = g.p_pad;
+      tp = false; tq = false;
+    } else {               // X' = a X + B X
+      a.P = B; a.strideP = g.s_stride; a.ldp = g.p_pad;
+      a.Q = X; a.strideQ = g.x_stride; a.ldq = g.cols_pad;
+      tp = false; tq = true;
+    }
+    a.symmetric = 0;
+    a.alpha = 1.0f; a.beta = hp.ns_a;
+    if (first) a.post = POST_INV;
+    if (last) {
+      a.epilogue = EPI_UPDATE;
+      a.store_out = (hp.flags & MONA_FLAG_KEEP_O) ? 1 : 0;
+      a.w_keep = 1.0f - hp.lr * hp.weight_decay;
+      a.o_scale = hp.lr * hp.gamma_coeff * sqrtf((float)std::max(g.m, g.n));
+    }
+  }
+  a.tiles_m = a.M / tile;
+  a.tiles_n = a.N / tile;
+  a.tiles_per_mat = a.symmetric ? a.tiles_n * (a.tiles_n + 1) / 2 : a.tiles_m * a.tiles_n;
+}
+
+int check_hparams(const mona_hparams* hp) {
+  if (!hp) return fail(MONA_EINVAL, "hparams is NULL");
+  if (!(hp->momentum >= 0.0f && hp->momentum < 1.0f)) return fail(MONA_EINVAL, "momentum must lie in [0, 1)");
+  if (!(hp->beta_a >= 0.0f && hp->beta_a < 1.0f)) return fail(MONA_EINVAL, "beta_a must lie in [0, 1)");
+  if (hp->ns_steps < 0) return fail(MONA_EINVAL, "ns_steps must be >= 0");
+  if (!std::isfinite(hp->lr) || !std::isfinite(hp->alpha) || !std::isfinite(hp->weight_decay) ||
+      !std::isfinite(hp->ns_a) || !std::isfinite(hp->ns_b) || !std::isfinite(hp->ns_c) ||
+      !std::isfinite(hp->gamma_coeff) || !std::isfinite(hp->ns_eps) || hp->ns_eps < 0.0f)
+    return fail(MONA_EINVAL, "hyper-parameters must be finite (and ns_eps >= 0)");
+  if (hp->flags & ~(MONA_FLAG_FIRST_DIFF_ZERO | MONA_FLAG_KEEP_O)) return fail(MONA_EINVAL, "unknown flag bits");
+  return MONA_OK;
+}
+
+bool get_event_pair(mona_state* st, hipEvent_t* a, hipEvent_t* b) {
+  if (st->pool_used == st->event_pool.size()) {
+    hipEvent_t x, y;
+    if (hipEventCreate(&x) != hipSuccess) return false;
+    if (hipEventCreate(&y) != hipSuccess) { (void)hipEventDestroy(x); return false; }
+    st->event_pool.emplace_back(x, y);
+  }
+  *a = st->event_pool[st->pool_used].first;
+  *b = st->event_pool[st->pool_used].second;
+  ++st->pool_used;
+  return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* mona_last_error(void) { return g_err.c_str(); }
+const char* mona_version(void) { return "libmona 0.1 (gfx950)"; }
+
+int mona_state_size(const mona_matrix* mats, int32_t count, const mona_options* opts, size_t* bytes_out) {
+  if (!bytes_out) return fail(MONA_EINVAL, "bytes_out is NULL");
+  int rc = check_mats(mats, count, false);
+  if (rc) return rc;
+  mona_options o;
+  rc = check_opts(opts, &o);
+  if (rc) return rc;
+  Layout L;
+  build_layout(mats, count, o, L);
+  *bytes_out = L.total;
+  return MONA_OK;
+}
+
+int mona_init_state(const mona_matrix* mats, int32_t count, const mona_options* opts, void* arena,
+                    size_t arena_bytes, void* stream, mona_state** out) {
+  if (!out) return fail(MONA_EINVAL, "out is NULL");
+  *out = nullptr;
+  int rc = check_mats(mats, count, false);
+  if (rc) return rc;
+  mona_options o;
+  rc = check_opts(opts, &o);
+  if (rc) return rc;
+  if (!arena) return fail(MONA_EINVAL, "arena is NULL");
+  if ((uintptr_t)arena % kAlign) return fail(MONA_EINVAL, "arena must be 256-byte aligned");
+  mona_state* st = new (std::nothrow) mona_state();
+  if (!st) return fail(MONA_ENOMEM, "host allocation failed");
+  build_layout(mats, count, o, st->L);
+  const Layout& L = st->L;
+  if (arena_bytes < L.total) {
+    const size_t need = L.total;
+    delete st;
+    return fail(MONA_ENOMEM, "arena too small: %zu bytes given, %zu needed", arena_bytes, need);
+  }
+  st->opt = o;
+  st->mats.assign(mats, mats + count);
+  st->arena = static_cast<char*>(arena);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+
+  auto cleanup = [&](int code) {
+    for (int i = 0; i < kRing; ++i) {
+      if (st->ring[i]) { (void)hipHostFree(st->ring[i]); (void)hipEventDestroy(st->ring_ev[i]); }
+    }
+    if (st->ev_valid) for (auto& e : st->ev) (void)hipEventDestroy(e);
+    delete st;
+    return code;
+  };
+#define INIT_TRY(expr)                                                                                   \
+  do {                                                                                                   \
+    hipError_t e__ = (expr);                                                                             \
+    if (e__ != hipSuccess) return cleanup(fail(MONA_EHIP, "%s: %s", #expr, hipGetErrorString(e__)));     \
+  } while (0)
+
+  INIT_TRY(hipGetDevice(&st->device));
+  for (int i = 0; i < kRing; ++i) {
+    void* p = nullptr;
+    INIT_TRY(hipHostMalloc(&p, sizeof(MatDynamic) * (size_t)count, hipHostMallocDefault));
+    st->ring[i] = static_cast<MatDynamic*>(p);
+    hipError_t e = hipEventCreateWithFlags(&st->ring_ev[i], hipEventDisableTiming);
+    if (e != hipSuccess) {
+      (void)hipHostFree(p);
+      st->ring[i] = nullptr;
+      return cleanup(fail(MONA_EHIP, "hipEventCreate: %s", hipGetErrorString(e)));
+    }
+  }
+  for (auto& e : st->ev) INIT_TRY(hipEventCreate(&e));
+  st->ev_valid = true;
+
+  // Alg. 1 initialisation: M_0 = A_0 = G_0 = 0; the padded working copies start (and stay) zero
+  INIT_TRY(launch_fill_zero(st->arena + L.state_begin, L.state_bytes + L.work_bytes, s));
+  INIT_TRY(launch_fill_zero(st->arena + L.scales_off, align_up(sizeof(MatScale) * count), s));
+
+  std::vector<MatStatic> stat(count);
+  std::vector<void*> optr(count);
+  for (int i = 0; i < count; ++i) {
+    const Group& g = L.groups[L.group_of[i]];
+    MatStatic& ms = stat[i];
+    memset(&ms, 0, sizeof ms);
+    ms.g_prev = st->arena + L.gprev_off[i];
+    ms.acc = st->arena + L.acc_off[i];
+    ms.mom = reinterpret_cast<float*>(st->arena + L.mom_off[i]);
+    ms.x = st->arena + g.x_off[0] + (size_t)L.rank_in_group[i] * g.x_stride * L.esize;
+    ms.m = mats[i].m;
+    ms.n = mats[i].n;
+    ms.ldx = g.cols_pad;
+    ms.w_dtype = mats[i].w_dtype;
+    ms.g_dtype = mats[i].g_dtype;
+    ms.first_block = L.first_block[i];
+    ms.num_blocks = L.num_blocks[i];
+    optr[i] = st->arena + g.x_off[1] + (size_t)L.rank_in_group[i] * g.x_stride * L.esize;
+  }
+  INIT_TRY(hipMemcpyAsync(st->arena + L.stat_off, stat.data(), sizeof(MatStatic) * count, hipMemcpyHostToDevice, s));
+  INIT_TRY(hipMemcpyAsync(st->arena + L.optr_off, optr.data(), sizeof(void*) * count, hipMemcpyHostToDevice, s));
+  INIT_TRY(hipMemcpyAsync(st->arena + L.blocks_off, L.blocks.data(), sizeof(BlockWork) * L.blocks.size(),
+                          hipMemcpyHostToDevice, s));
+  for (const Group& g : L.groups) {
+    std::vector<int32_t> mem(g.members.begin(), g.members.end());
+    INIT_TRY(hipMemcpyAsync(st->arena + g.members_off, mem.data(), sizeof(int32_t) * mem.size(),
+                            hipMemcpyHostToDevice, s));
+    INIT_TRY(hipStreamSynchronize(s));   // `mem` leaves scope
+  }
+  INIT_TRY(hipStreamSynchronize(s));     // host vectors above leave scope
+#undef INIT_TRY
+  *out = st;
+  return MONA_OK;
+}
+
+int mona_step(mona_state* st, const mona_matrix* mats, int32_t count, const mona_hparams* hp, void* stream) {
+  if (!st) return fail(MONA_EINVAL, "state is NULL");
+  int rc = check_mats(mats, count, true);
+  if (rc) return rc;
+  rc = check_hparams(hp);
+  if (rc) return rc;
+  const Layout& L = st->L;
+  if (count != L.count) return fail(MONA_ESHAPE, "count %d differs from %d at init", count, L.count);
+  for (int i = 0; i < count; ++i) {
+    const mona_matrix& a = mats[i];
+    const mona_matrix& b = st->mats[i];
+    if (a.m != b.m || a.n != b.n || a.w_dtype != b.w_dtype || a.g_dtype != b.g_dtype)
+      return fail(MONA_ESHAPE, "matrix %d: shape or dtype differs from init (%d x %d vs %d x %d)", i, a.m, a.n, b.m,
+                  b.n);
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const bool f32 = st->opt.ns_precision == 1;
+
+  // per-step pointer table
+  bool changed = !st->dyn_valid;
+  if (!changed)
+    for (int i = 0; i < count; ++i)
+      if (st->last_dyn[i].w != mats[i].w || st->last_dyn[i].g != mats[i].g) { changed = true; break; }
+  if (changed) {
+    const int slot = st->ring_next;
+    if (st->ring_used[slot]) HIP_TRY(hipEventSynchronize(st->ring_ev[slot]));
+    st->last_dyn.resize(count);
+    for (int i = 0; i < count; ++i) {
+      st->last_dyn[i].w = mats[i].w;
+      st->last_dyn[i].g = mats[i].g;
+      st->ring[slot][i] = st->last_dyn[i];
+    }
+    HIP_TRY(hipMemcpyAsync(st->arena + L.dyn_off, st->ring[slot], sizeof(MatDynamic) * count, hipMemcpyHostToDevice,
+                           s));
+    HIP_TRY(hipEventRecord(st->ring_ev[slot], s));
+    st->ring_used[slot] = true;
+    st->ring_next = (slot + 1) % kRing;
+    st->dyn_valid = true;
+  }
+
+  const MatStatic* stat = st->at<MatStatic>(L.stat_off);
+  const MatDynamic* dyn = st->at<MatDynamic>(L.dyn_off);
+  MatScale* scales = st->at<MatScale>(L.scales_off);
+  float* partials = st->at<float>(L.partials_off);
+  const BlockWork* blocks = st->at<BlockWork>(L.blocks_off);
+  const int nblocks = (int)L.blocks.size();
+
+  const bool prof = st->profiling > 0;
+  st->times_ready = false;
+  st->records.clear();
+  st->pool_used = 0;
+  if (prof) HIP_TRY(hipEventRecord(st->ev[0], s));
+
+  // Alg. 1: difference, acceleration EMA, accelerated gradient, momentum, roll; sum of squares
+  const int use_prev = !((hp->flags & MONA_FLAG_FIRST_DIFF_ZERO) && st->k == 0);
+  const int sbf = st->opt.state_dtype == MONA_BF16;
+  HIP_TRY(launch_state_update(stat, dyn, blocks, partials, L.blocks_f32g, 0, sbf, f32, hp->momentum, hp->beta_a,
+                              hp->alpha, use_prev, s));
+  HIP_TRY(launch_state_update(stat, dyn, blocks + L.blocks_f32g, partials + L.blocks_f32g, nblocks - L.blocks_f32g, 1,
+                              sbf, f32, hp->momentum, hp->beta_a, hp->alpha, use_prev, s));
+  HIP_TRY(launch_norm_finalize(stat, partials, scales, count, hp->ns_eps, s));
+  if (prof) HIP_TRY(hipEventRecord(st->ev[1], s));
+
+  // Newton-Schulz (Eq. newton_schulz), T iterations of Gram / poly / apply per shape group
+  const int T = hp->ns_steps;
+  st->fused_update = T > 0;
+  st->o_buf = (T == 0) ? 1 : (T & 1);
+  for (size_t gi = 0; gi < L.groups.size(); ++gi) {
+    const Group& g = L.groups[gi];
+    const int cnt = (int)g.members.size();
+    int src = 0;
+    for (int t = 0; t < T; ++t) {
+      for (int kind = OP_GRAM; kind <= OP_APPLY; ++kind) {
+        GemmArgs a;
+        bool tp = false, tq = false;
+        const int tile = pick_tile(g, kind, cnt, f32);
+        fill_gemm(st, g, kind, tile, src, *hp, t == 0, t == T - 1, a, tp, tq);
+        LaunchRecord rec;
+        const bool each = st->profiling > 1;
+        if (each) {
+          if (!get_event_pair(st, &rec.e0, &rec.e1)) return fail(MONA_EHIP, "hipEventCreate failed");
+          HIP_TRY(hipEventRecord(rec.e0, s));
+        }
+        HIP_TRY(launch_ns_gemm(a, tile, tp, tq, f32, s));
+        if (each) {
+          HIP_TRY(hipEventRecord(rec.e1, s));
+          rec.kind = kind; rec.group = (int)gi; rec.iter = t; rec.tile = tile;
+          rec.flops = gemm_flops(a, tile);
+          st->records.push_back(rec);
+        }
+      }
+      src ^= 1;
+    }
+  }
+  if (prof) HIP_TRY(hipEventRecord(st->ev[2], s));
+  if (T == 0) {
+    // O = X_0, then Eq. muon_update
+    HIP_TRY(launch_plain_update(stat, dyn, scales, blocks, nblocks, f32, st->at<void*>(L.optr_off), hp->lr,
+                                hp->weight_decay, hp->gamma_coeff, (hp->flags & MONA_FLAG_KEEP_O) ? 1 : 0, s));
+  }
+  if (prof) {
+    HIP_TRY(hipEventRecord(st->ev[3], s));
+    st->times_ready = true;
+  }
+  st->k += 1;
+  return MONA_OK;
+}
+
+int mona_free_state(mona_state* st) {
+  if (!st) return MONA_OK;
+  for (int i = 0; i < kRing; ++i) {
+    if (st->ring_used[i]) (void)hipEventSynchronize(st->ring_ev[i]);
+    if (st->ring[i]) { (void)hipHostFree(st->ring[i]); (void)hipEventDestroy(st->ring_ev[i]); }
+  }
+  if (st->ev_valid) for (auto& e : st->ev) (void)hipEventDestroy(e);
+  for (auto& pr : st->event_pool) { (void)hipEventDestroy(pr.first); (void)hipEventDestroy(pr.second); }
+  delete st;
+  return MONA_OK;
+}
+
+int mona_state_view(mona_state* st, int32_t i, int32_t kind, mona_view* out) {
+  if (!st || !out) return fail(MONA_EINVAL, "state or out is NULL");
+  const Layout& L = st->L;
+  if (i < 0 || i >= L.count) return fail(MONA_EINVAL, "matrix index %d out of range [0, %d)", i, L.count);
+  const mona_matrix& q = st->mats[i];
+  const Group& g = L.groups[L.group_of[i]];
+  out->rows = q.m; out->cols = q.n; out->ld = q.n;
+  switch (kind) {
+    case MONA_VIEW_G_PREV: out->ptr = st->arena + L.gprev_off[i]; out->dtype = st->opt.state_dtype; break;
+    case MONA_VIEW_A: out->ptr = st->arena + L.acc_off[i]; out->dtype = st->opt.state_dtype; break;
+    case MONA_VIEW_M: out->ptr = st->arena + L.mom_off[i]; out->dtype = MONA_F32; break;
+    case MONA_VIEW_NORM:
+      out->ptr = reinterpret_cast<char*>(st->at<MatScale>(L.scales_off) + i) + offsetof(MatScale, norm);
+      out->rows = out->cols = out->ld = 1; out->dtype = MONA_F32;
+      break;
+    case MONA_VIEW_O: {
+      // iteration t reads buffer t % 2 and writes the other one; with T = 0 the update kernel
+      // writes buffer 1
+      out->ptr = st->arena + g.x_off[st->o_buf] + (size_t)L.rank_in_group[i] * g.x_stride * L.esize;
+      out->ld = g.cols_pad;
+      out->dtype = st->opt.ns_precision == 1 ? MONA_F32 : MONA_BF16;
+      break;
+    }
+    default: return fail(MONA_EINVAL, "unknown view kind %d", kind);
+  }
+  return MONA_OK;
+}
+
+int mona_state_export_size(mona_state* st, size_t* bytes_out) {
+  if (!st || !bytes_out) return fail(MONA_EINVAL, "state or bytes_out is NULL");
+  *bytes_out = st->L.state_bytes;
+  return MONA_OK;
+}
+
+int mona_state_export(mona_state* st, void* dst, size_t dst_bytes, void* stream) {
+  if (!st || !dst) return fail(MONA_EINVAL, "state or dst is NULL");
+  if (dst_bytes < st->L.state_bytes) return fail(MONA_ENOMEM, "dst too small: %zu < %zu", dst_bytes, st->L.state_bytes);
+  HIP_TRY(hipMemcpyAsync(dst, st->arena + st->L.state_begin, st->L.state_bytes, hipMemcpyDeviceToDevice,
+                         static_cast<hipStream_t>(stream)));
+  return MONA_OK;
+}
+
+int mona_state_import(mona_state* st, const void* src, size_t src_bytes, int64_t step_count, void* stream) {
+  if (!st || !src) return fail(MONA_EINVAL, "state or src is NULL");
+  if (src_bytes != st->L.state_bytes)
+    return fail(MONA_ESHAPE, "checkpoint holds %zu bytes, this state needs %zu", src_bytes, st->L.state_bytes);
+  if (step_count < 0) return fail(MONA_EINVAL, "step_count must be >= 0");
+  HIP_TRY(hipMemcpyAsync(st->arena + st->L.state_begin, src, st->L.state_bytes, hipMemcpyDeviceToDevice,
+                         static_cast<hipStream_t>(stream)));
+  st->k = step_count;
+  return MONA_OK;
+}
+
+int mona_state_step_count(mona_state* st, int64_t* k_out) {
+  if (!st || !k_out) return fail(MONA_EINVAL, "state or k_out is NULL");
+  *k_out = st->k;
+  return MONA_OK;
+}
+
+int mona_state_status(mona_state* st, uint32_t* host_out, int32_t count, void* stream) {
+  if (!st || !host_out) return fail(MONA_EINVAL, "state or host_out is NULL");
+  if (count != st->L.count) return fail(MONA_ESHAPE, "count %d differs from %d at init", count, st->L.count);
+  std::vector<MatScale> tmp(count);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  HIP_TRY(hipMemcpyAsync(tmp.data(), st->arena + st->L.scales_off, sizeof(MatScale) * count, hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  for (int i = 0; i < count; ++i) host_out[i] = tmp[i].status;
+  return MONA_OK;
+}
+
+int mona_set_profiling(mona_state* st, int32_t on) {
+  if (!st) return fail(MONA_EINVAL, "state is NULL");
+  if (on < 0 || on > 2) return fail(MONA_EINVAL, "profiling level must be 0, 1 or 2");
+  st->profiling = on;
+  st->times_ready = false;
+  return MONA_OK;
+}
+
+int mona_last_step_times(mona_state* st, float* ms_out) {
+  if (!st || !ms_out) return fail(MONA_EINVAL, "state or ms_out is NULL");
+  if (!st->times_ready) return fail(MONA_EINVAL, "no profiled step yet (call mona_set_profiling(st, 1) first)");
+  HIP_TRY(hipEventSynchronize(st->ev[3]));
+  HIP_TRY(hipEventElapsedTime(&ms_out[0], st->ev[0], st->ev[1]));
+  HIP_TRY(hipEventElapsedTime(&ms_out[1], st->ev[1], st->ev[2]));
+  HIP_TRY(hipEventElapsedTime(&ms_out[2], st->ev[2], st->ev[3]));
+  HIP_TRY(hipEventElapsedTime(&ms_out[3], st->ev[0], st->ev[3]));
+  return MONA_OK;
+}
+
+int mona_last_step_launches(mona_state* st, mona_launch_time* out, int32_t max_records, int32_t* n_out) {
+  if (!st || !n_out) return fail(MONA_EINVAL, "state or n_out is NULL");
+  if (st->profiling < 2 || !st->times_ready) return fail(MONA_EINVAL, "no step profiled at level 2 yet");
+  HIP_TRY(hipEventSynchronize(st->ev[3]));
+  const int n = (int)st->records.size();
+  *n_out = n;
+  if (!out) return MONA_OK;
+  for (int i = 0; i < n && i < max_records; ++i) {
+    const LaunchRecord& r = st->records[i];
+    out[i].kind = r.kind; out[i].group = r.group; out[i].iter = r.iter; out[i].tile = r.tile;
+    out[i].flops = r.flops;
+    const Group& g = st->L.groups[r.group];
+    out[i].m = g.m; out[i].n = g.n; out[i].count = (int)g.members.size();
+    HIP_TRY(hipEventElapsedTime(&out[i].ms, r.e0, r.e1));
+  }
+  return MONA_OK;
+}
+
+int mona_plan_info(mona_state* st, int32_t ns_steps, int64_t* launches_out, double* ns_flops_executed_out,
+                   double* elementwise_bytes_out) {
+  if (!st) return fail(MONA_EINVAL, "state is NULL");
+  if (ns_steps < 0) return fail(MONA_EINVAL, "ns_steps must be >= 0");
+  const Layout& L = st->L;
+  const bool f32 = st->opt.ns_precision == 1;
+  mona_hparams hp;
+  memset(&hp, 0, sizeof hp);
+  double flops = 0.0;
+  int64_t launches = 0;
+  for (const Group& g : L.groups) {
+    const int cnt = (int)g.members.size();
+    for (int kind = OP_GRAM; kind <= OP_APPLY; ++kind) {
+      GemmArgs a;
+      bool tp, tq;
+      const int tile = pick_tile(g, kind, cnt, f32);
+      fill_gemm(st, g, kind, tile, 0, hp, false, false, a, tp, tq);
+      flops += gemm_flops(a, tile) * ns_steps;
+      launches += ns_steps;
+    }
+  }
+  double bytes = 0.0;
+  for (int i = 0; i < L.count; ++i) {
+    const double ne = (double)st->mats[i].m * st->mats[i].n;
+    const double gsz = st->mats[i].g_dtype == MONA_BF16 ? 2 : 4;
+    // state pass: read G, G_prev, A, M; write G_prev, A, M and the working copy of M
+    bytes += ne * (gsz + 2 * L.ssize + 4 + 2 * L.ssize + 4 + L.esize);
+  }
+  if (launches_out) *launches_out = launches;
+  if (ns_flops_executed_out) *ns_flops_executed_out = flops;
+  if (elementwise_bytes_out) *elementwise_bytes_out = bytes;
+  return MONA_OK;
+}
+
+}  // extern "C"

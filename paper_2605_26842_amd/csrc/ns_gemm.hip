@@ -1,0 +1,468 @@
+// Matrix products of the Newton-Schulz iteration (Eq. newton_schulz), written as three
+// products per iteration on the short side p = min(m, n) of each matrix:
+//
+//     S   = X X^T                (p x p, symmetric)          "Gram"
+//     B   = b S + c S S          (p x p, symmetric)          "poly"
+//     X'  = a X + B X            (p x q)                     "apply"
+//
+// (for a tall matrix stored m x n with m > n the same polynomial is S = X^T X,
+// X' = a X + X B, because the quintic is odd).  Every product has the form
+//
+//     out = post * (beta * E + alpha * P Q^T),     P: M x K,  Q: N x K
+//
+// over a batch of same-shape matrices.  An operand may be stored K-major (K x M); it is then
+// transposed in registers on its way into LDS, so the MFMA loop below always reads K-contiguous
+// rows.  All dimensions are padded by the host to multiples of the tile and the padding is kept
+// zero, so the main loop has no bounds checks.
+//
+// bf16 path: v_mfma_f32_32x32x16_bf16, fp32 accumulation, 256 threads = 4 wavefronts in a
+// 2 x 2 arrangement, block tile BM x BN (256 x 256 or 128 x 128), K step 64, LDS double buffer.
+// fp32 path: v_mfma_f32_32x32x2_f32, 128 x 128 tiles, K step 16.
+#include "mona_internal.h"
+
+namespace mona {
+
+namespace {
+
+typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
+typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kThreads = 256;
+constexpr int kXcds = 8;   // MI355X: 8 accelerator dies, workgroups are dealt to them round-robin
+
+// compile-time loop: f(integral_constant<int, 0>), ..., f(integral_constant<int, N - 1>)
+template <int I> struct IC { static constexpr int value = I; constexpr operator int() const { return I; } };
+template <int N, int I = 0, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(IC<I>{});
+    static_for<N, I + 1>(f);
+  }
+}
+
+// ---- tile decode ---------------------------------------------------------------------
+struct TileId {
+  int mat, ti, tj;
+  bool valid;
+};
+
+// Workgroup L runs on die L % 8.  Give every die one contiguous range of the logical tile
+// order (matrix-major), so that tiles that share operands share that die's L2.
+__device__ __forceinline__ TileId decode_tile(const GemmArgs& a) {
+  TileId t;
+  const int total = a.tiles_per_mat * a.count;
+  const int per_xcd = gridDim.x / kXcds;
+  const int logical = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+  t.valid = logical < total;
+  t.mat = logical / a.tiles_per_mat;
+  int r = logical - t.mat * a.tiles_per_mat;
+  if (a.symmetric) {
+    int ti = 0, row = a.tiles_n;
+    while (r >= row) { r -= row; --row; ++ti; }
+    t.ti = ti;
+    t.tj = ti + r;
+  } else {
+    t.ti = r / a.tiles_n;
+    t.tj = r - t.ti * a.tiles_n;
+  }
+  return t;
+}
+
+// ---- LDS layout ------------------------------------------------------------------------
+// An operand tile is R rows of 64 bf16 (128 bytes = 8 chunks of 16 bytes).  The chunk index is
+// XOR-swizzled with the row so that 16 consecutive rows at one logical chunk fall on 16
+// different 16-byte bank groups (the fragment read), as do 2 rows x 8 chunks (the tile store).
+__device__ __forceinline__ int lds_slot(int row, int chunk) {
+  return row * 8 + (chunk ^ ((row & 7) ^ ((row >> 3) & 1)));
+}
+
+__device__ __forceinline__ uint32_t pack_lo(uint32_t x, uint32_t y) {  // (x.lo16, y.lo16)
+  return __builtin_amdgcn_perm(y, x, 0x05040100u);
+}
+__device__ __forceinline__ uint32_t pack_hi(uint32_t x, uint32_t y) {  // (x.hi16, y.hi16)
+  return __builtin_amdgcn_perm(y, x, 0x07060302u);
+}
+
+// ---- operand loaders (global -> registers -> LDS) ---------------------------------------
+// R: rows of the tile (BM or BN).  Each thread moves R/32 chunks of 16 bytes per K step.
+template <int R, bool TRANS>
+struct Loader {
+  static constexpr int kRegs = R / 32;
+  u32x4 v[kRegs];
+
+  // src: first element of this matrix; r0: first tile row; k0: first k; ld: leading dimension
+  __device__ __forceinline__ void load(const bf16_t* __restrict__ src, int ld, int r0, int k0) {
+    const int tid = threadIdx.x;
+    if constexpr (!TRANS) {
+      const int chunk = tid & 7, row = tid >> 3;
+      static_for<kRegs>([&](auto i) {
+        v[i] = *reinterpret_cast<const u32x4*>(src + (size_t)(r0 + row + 32 * i) * ld + k0 + chunk * 8);
+      });
+    } else {
+      // K-major storage: element (k, r) at src[k * ld + r].  Each thread takes kRegs consecutive
+      // k-rows of 8 consecutive r.
+      constexpr int kKB = 64 / kRegs;           // k-blocks per K step
+      const int kb = tid % kKB, rb = tid / kKB;
+      static_for<kRegs>([&](auto i) {
+        v[i] = *reinterpret_cast<const u32x4*>(src + (size_t)(k0 + kb * kRegs + i) * ld + r0 + rb * 8);
+      });
+    }
+  }
+
+  __device__ __forceinline__ void store(u32x4* __restrict__ lds) const {
+    const int tid = threadIdx.x;
+    if constexpr (!TRANS) {
+      const int chunk = tid & 7, row = tid >> 3;
+      static_for<kRegs>([&](auto i) { lds[lds_slot(row + 32 * i, chunk)] = v[i]; });
+    } else {
+      constexpr int kKB = 64 / kRegs;
+      const int kb = tid % kKB, rb = tid / kKB;
+      // transpose the kRegs x 8 block held in v[] to 8 rows of kRegs k-values
+      // word(i, cw): 32-bit word cw of k-row i, i.e. columns 2 cw and 2 cw + 1
+      auto word = [&](int i, int cw) -> uint32_t {
+        return cw == 0 ? v[i].x : cw == 1 ? v[i].y : cw == 2 ? v[i].z : v[i].w;
+      };
+      if constexpr (kRegs == 8) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+          u32x4 o;
+          const int cw = c >> 1;
+          if ((c & 1) == 0) {
+            o.x = pack_lo(word(0, cw), word(1, cw));
+            o.y = pack_lo(word(2, cw), word(3, cw));
+            o.z = pack_lo(word(4, cw), word(5, cw));
+            o.w = pack_lo(word(6, cw), word(7, cw));
+          } else {
+            o.x = pack_hi(word(0, cw), word(1, cw));
+            o.y = pack_hi(word(2, cw), word(3, cw));
+            o.z = pack_hi(word(4, cw), word(5, cw));
+            o.w = pack_hi(word(6, cw), word(7, cw));
+          }
+          lds[lds_slot(rb * 8 + c, kb)] = o;
+        }
+      } else {
+        static_assert(kRegs == 4 || kRegs == 8, "tile rows must be 128 or 256");
+        // 4 k-values per row: half a chunk
+        u32x2* lds2 = reinterpret_cast<u32x2*>(lds);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+          u32x2 o;
+          const int cw = c >> 1;
+          if ((c & 1) == 0) {
+            o.x = pack_lo(word(0, cw), word(1, cw));
+            o.y = pack_lo(word(2, cw), word(3, cw));
+          } else {
+            o.x = pack_hi(word(0, cw), word(1, cw));
+            o.y = pack_hi(word(2, cw), word(3, cw));
+          }
+          lds2[lds_slot(rb * 8 + c, kb >> 1) * 2 + (kb & 1)] = o;
+        }
+      }
+    }
+  }
+};
+
+__device__ __forceinline__ float to_f32(bf16_t v) { return (float)v; }
+__device__ __forceinline__ float to_f32(float v) { return v; }
+
+// ---- epilogue -----------------------------------------------------------------------------
+// acc[v] of a 32x32 MFMA block: row = (v / 4) * 8 + (lane / 32) * 4 + (v % 4), col = lane % 32.
+template <typename T>
+__device__ __forceinline__ void epilogue_block(const GemmArgs& a, const f32x16& acc, int mat, int row0,
+                                               int col0, bool mirror, float post, const T* __restrict__ E,
+                                               T* __restrict__ C, const MatStatic* ms, void* wptr,
+                                               bool skip_w) {
+  const int lane = threadIdx.x & 63;
+  const int col = col0 + (lane & 31);
+  const int rbase = row0 + (lane >> 5) * 4;
+#pragma unroll
+  for (int vg = 0; vg < 4; ++vg) {
+    float o[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int row = rbase + vg * 8 + e;
+      float val = a.alpha * acc[vg * 4 + e];
+      if (E != nullptr) val += a.beta * to_f32(E[(size_t)row * a.lde + col]);
+      o[e] = post * val;
+    }
+    if (a.epilogue == EPI_STORE) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) C[(size_t)(rbase + vg * 8 + e) * a.ldc + col] = (T)o[e];
+      if (mirror) {
+        // the transposed tile: 4 consecutive rows of this lane become 4 consecutive columns
+        T* dst = C + (size_t)col * a.ldc + rbase + vg * 8;
+        if constexpr (sizeof(T) == 2) {
+          bf16x4 pk = {(bf16_t)o[0], (bf16_t)o[1], (bf16_t)o[2], (bf16_t)o[3]};
+          *reinterpret_cast<bf16x4*>(dst) = pk;
+        } else {
+          f32x4 pk = {o[0], o[1], o[2], o[3]};
+          *reinterpret_cast<f32x4*>(dst) = pk;
+        }
+      }
+    } else {
+      // O_k = out; W <- (1 - eta lambda) W - eta gamma O   (Eq. muon_update), inside the real m x n
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int row = rbase + vg * 8 + e;
+        const float ov = to_f32((T)o[e]);     // O_k as stored in the working precision
+        if (a.store_out) C[(size_t)row * a.ldc + col] = (T)ov;
+        if (!skip_w && row < ms->m && col < ms->n) {
+          const size_t wi = (size_t)row * ms->n + col;
+          if (ms->w_dtype == 1) {
+            bf16_t* w = static_cast<bf16_t*>(wptr);
+            w[wi] = (bf16_t)(a.w_keep * (float)w[wi] - a.o_scale * ov);
+          } else {
+            float* w = static_cast<float*>(wptr);
+            w[wi] = a.w_keep * w[wi] - a.o_scale * ov;
+          }
+        }
+      }
+    }
+  }
+}
+
+// ---- bf16 kernel -----------------------------------------------------------------------------
+template <int BM, int BN, bool TP, bool TQ>
+__global__ __launch_bounds__(kThreads) void ns_gemm_bf16_kernel(const GemmArgs a) {
+  constexpr int BK = 64;
+  constexpr int WM = BM / 2, WN = BN / 2;   // per-wavefront tile
+  constexpr int MI = WM / 32, NI = WN / 32; // MFMA blocks per wavefront
+  __shared__ __attribute__((aligned(16))) u32x4 lds[2][(BM + BN) * 8];
+
+  const TileId t = decode_tile(a);
+  if (!t.valid) return;
+
+  const bf16_t* __restrict__ P = static_cast<const bf16_t*>(a.P) + (size_t)t.mat * a.strideP;
+  const bf16_t* __restrict__ Q = static_cast<const bf16_t*>(a.Q) + (size_t)t.mat * a.strideQ;
+  const int m0 = t.ti * BM, n0 = t.tj * BN;
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  f32x16 acc[MI][NI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+  Loader<BM, TP> lp;
+  Loader<BN, TQ> lq;
+  const int KT = a.K / BK;
+
+  lp.load(P, a.ldp, m0, 0);
+  lq.load(Q, a.ldq, n0, 0);
+  lp.store(lds[0]);
+  lq.store(lds[0] + BM * 8);
+  __syncthreads();
+
+  const int frow = lane & 31, fchunk = lane >> 5;
+  for (int kt = 0; kt < KT; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < KT) {
+      lp.load(P, a.ldp, m0, (kt + 1) * BK);
+      lq.load(Q, a.ldq, n0, (kt + 1) * BK);
+    }
+    const u32x4* __restrict__ lp_s = lds[buf];
+    const u32x4* __restrict__ lq_s = lds[buf] + BM * 8;
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      bf16x8 fa[MI], fb[NI];
+#pragma unroll
+      for (int i = 0; i < MI; ++i) {
+        const u32x4 u = lp_s[lds_slot(wm * WM + i * 32 + frow, kk * 2 + fchunk)];
+        fa[i] = __builtin_bit_cast(bf16x8, u);
+      }
+#pragma unroll
+      for (int j = 0; j < NI; ++j) {
+        const u32x4 u = lq_s[lds_slot(wn * WN + j * 32 + frow, kk * 2 + fchunk)];
+        fb[j] = __builtin_bit_cast(bf16x8, u);
+      }
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < KT) {
+      lp.store(lds[buf ^ 1]);
+      lq.store(lds[buf ^ 1] + BM * 8);
+    }
+    __syncthreads();
+  }
+
+  // epilogue
+  const int mi = a.members ? a.members[t.mat] : t.mat;
+  float post = 1.0f;
+  if (a.post == POST_INV) post = a.scales[mi].inv;
+  else if (a.post == POST_INV2) post = a.scales[mi].inv2;
+  const bf16_t* E = a.E ? static_cast<const bf16_t*>(a.E) + (size_t)t.mat * a.strideE : nullptr;
+  bf16_t* C = static_cast<bf16_t*>(a.C) + (size_t)t.mat * a.strideC;
+  const MatStatic* ms = nullptr;
+  void* wptr = nullptr;
+  bool skip_w = false;
+  if (a.epilogue == EPI_UPDATE) {
+    ms = a.stat + mi;
+    wptr = a.dyn[mi].w;
+    skip_w = (a.scales[mi].status & 2u) != 0;
+  }
+  const bool mirror = a.symmetric && (t.ti != t.tj);
+  static_for<MI>([&](auto i) {
+    static_for<NI>([&](auto j) {
+      epilogue_block<bf16_t>(a, acc[i][j], t.mat, m0 + wm * WM + i * 32, n0 + wn * WN + j * 32, mirror, post, E,
+                             C, ms, wptr, skip_w);
+    });
+  });
+}
+
+// ---- fp32 kernel ------------------------------------------------------------------------------
+// 128 x 128 tile, K step 16.  LDS holds each operand k-major ([k][row], padded) so a fragment
+// read (32 consecutive rows at one k) is conflict-free.
+template <bool TP, bool TQ>
+__global__ __launch_bounds__(kThreads) void ns_gemm_f32_kernel(const GemmArgs a) {
+  constexpr int BM = 128, BN = 128, BK = 16;
+  constexpr int LDR = 128 + 4;   // padded row count per k
+  __shared__ float lds[2][2][BK * LDR];
+
+  const TileId t = decode_tile(a);
+  if (!t.valid) return;
+  const float* __restrict__ P = static_cast<const float*>(a.P) + (size_t)t.mat * a.strideP;
+  const float* __restrict__ Q = static_cast<const float*>(a.Q) + (size_t)t.mat * a.strideQ;
+  const int m0 = t.ti * BM, n0 = t.tj * BN;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int tid = threadIdx.x;
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+  // each thread moves 2 x float4 per operand per K step
+  f32x4 rp[2], rq[2];
+  auto gload = [&](const float* __restrict__ src, int ld, int r0, int k0, bool trans, f32x4* r) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int id = tid + i * kThreads;               // 0..511 float4 slots of a 128 x 16 tile
+      if (!trans) {
+        const int row = id >> 2, kq = id & 3;          // 4 float4 per row (16 k)
+        r[i] = *reinterpret_cast<const f32x4*>(src + (size_t)(r0 + row) * ld + k0 + kq * 4);
+      } else {
+        const int k = id >> 5, rq4 = id & 31;          // 32 float4 per k-row (128 rows)
+        r[i] = *reinterpret_cast<const f32x4*>(src + (size_t)(k0 + k) * ld + r0 + rq4 * 4);
+      }
+    }
+  };
+  auto lstore = [&](float* __restrict__ dst, bool trans, const f32x4* r) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int id = tid + i * kThreads;
+      if (!trans) {
+        const int row = id >> 2, kq = id & 3;
+        dst[(kq * 4 + 0) * LDR + row] = r[i].x;
+        dst[(kq * 4 + 1) * LDR + row] = r[i].y;
+        dst[(kq * 4 + 2) * LDR + row] = r[i].z;
+        dst[(kq * 4 + 3) * LDR + row] = r[i].w;
+      } else {
+        const int k = id >> 5, rq4 = id & 31;
+        *reinterpret_cast<f32x4*>(dst + k * LDR + rq4 * 4) = r[i];
+      }
+    }
+  };
+
+  const int KT = a.K / BK;
+  gload(P, a.ldp, m0, 0, TP, rp);
+  gload(Q, a.ldq, n0, 0, TQ, rq);
+  lstore(lds[0][0], TP, rp);
+  lstore(lds[0][1], TQ, rq);
+  __syncthreads();
+  const int frow = lane & 31, fk = lane >> 5;
+  for (int kt = 0; kt < KT; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < KT) {
+      gload(P, a.ldp, m0, (kt + 1) * BK, TP, rp);
+      gload(Q, a.ldq, n0, (kt + 1) * BK, TQ, rq);
+    }
+    const float* __restrict__ sp = lds[buf][0];
+    const float* __restrict__ sq = lds[buf][1];
+#pragma unroll
+    for (int kk = 0; kk < BK / 2; ++kk) {
+      float fa[2], fb[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) fa[i] = sp[(kk * 2 + fk) * LDR + wm * 64 + i * 32 + frow];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) fb[j] = sq[(kk * 2 + fk) * LDR + wn * 64 + j * 32 + frow];
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < KT) {
+      lstore(lds[buf ^ 1][0], TP, rp);
+      lstore(lds[buf ^ 1][1], TQ, rq);
+    }
+    __syncthreads();
+  }
+
+  const int mi = a.members ? a.members[t.mat] : t.mat;
+  float post = 1.0f;
+  if (a.post == POST_INV) post = a.scales[mi].inv;
+  else if (a.post == POST_INV2) post = a.scales[mi].inv2;
+  const float* E = a.E ? static_cast<const float*>(a.E) + (size_t)t.mat * a.strideE : nullptr;
+  float* C = static_cast<float*>(a.C) + (size_t)t.mat * a.strideC;
+  const MatStatic* ms = nullptr;
+  void* wptr = nullptr;
+  bool skip_w = false;
+  if (a.epilogue == EPI_UPDATE) {
+    ms = a.stat + mi;
+    wptr = a.dyn[mi].w;
+    skip_w = (a.scales[mi].status & 2u) != 0;
+  }
+  const bool mirror = a.symmetric && (t.ti != t.tj);
+  static_for<2>([&](auto i) {
+    static_for<2>([&](auto j) {
+      epilogue_block<float>(a, acc[i][j], t.mat, m0 + wm * 64 + i * 32, n0 + wn * 64 + j * 32, mirror, post, E, C,
+                            ms, wptr, skip_w);
+    });
+  });
+}
+
+template <int BM, int BN>
+hipError_t launch_bf16(const GemmArgs& a, bool tp, bool tq, int grid, hipStream_t s) {
+  if (!tp && !tq) hipLaunchKernelGGL((ns_gemm_bf16_kernel<BM, BN, false, false>), dim3(grid), dim3(kThreads), 0, s, a);
+  else if (!tp && tq) hipLaunchKernelGGL((ns_gemm_bf16_kernel<BM, BN, false, true>), dim3(grid), dim3(kThreads), 0, s, a);
+  else if (tp && tq) hipLaunchKernelGGL((ns_gemm_bf16_kernel<BM, BN, true, true>), dim3(grid), dim3(kThreads), 0, s, a);
+  else return hipErrorInvalidValue;   // (transposed P, plain Q) never occurs in the plan
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_ns_gemm(const GemmArgs& a, int tile, bool transP, bool transQ, bool f32, hipStream_t s) {
+  const long long total = (long long)a.tiles_per_mat * a.count;
+  if (total <= 0) return hipSuccess;
+  if (total > 0x7fffff00LL) return hipErrorInvalidValue;
+  const int grid = (int)((total + kXcds - 1) / kXcds) * kXcds;
+  if (f32) {
+    if (tile != 128) return hipErrorInvalidValue;
+    if (!transP && !transQ) hipLaunchKernelGGL((ns_gemm_f32_kernel<false, false>), dim3(grid), dim3(kThreads), 0, s, a);
+    else if (!transP && transQ) hipLaunchKernelGGL((ns_gemm_f32_kernel<false, true>), dim3(grid), dim3(kThreads), 0, s, a);
+    else if (transP && transQ) hipLaunchKernelGGL((ns_gemm_f32_kernel<true, true>), dim3(grid), dim3(kThreads), 0, s, a);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+  }
+  if (tile == 256) return launch_bf16<256, 256>(a, transP, transQ, grid, s);
+  if (tile == 128) return launch_bf16<128, 128>(a, transP, transQ, grid, s);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace mona

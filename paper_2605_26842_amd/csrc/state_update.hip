@@ -1,0 +1,284 @@
+// Elementwise part of the MONA step (Alg. 1: difference, acceleration EMA, accelerated
+// gradient, momentum, state roll) fused with the sum of squares that the Newton-Schulz
+// prescale X_0 = M / ||M||_F needs (Sec. 3.2).  One pass over the state: every array is
+// read once and written once, 16 bytes per lane, so the kernel runs at HBM speed.
+//
+// Per element, with fp32 G and fp32 state: reads G, G_{k-1}, A, M (16 B), writes G_{k-1}, A, M
+// (12 B) and the bf16 copy of M that the matrix products read (2 B): 30 B.
+#include "mona_internal.h"
+
+namespace mona {
+
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ f32x4 load4(const float* p) { return *reinterpret_cast<const f32x4*>(p); }
+__device__ __forceinline__ f32x4 load4(const bf16_t* p) {
+  bf16x4 v = *reinterpret_cast<const bf16x4*>(p);
+  f32x4 r = {(float)v.x, (float)v.y, (float)v.z, (float)v.w};
+  return r;
+}
+__device__ __forceinline__ void store4(float* p, f32x4 v) { *reinterpret_cast<f32x4*>(p) = v; }
+__device__ __forceinline__ void store4(bf16_t* p, f32x4 v) {
+  bf16x4 r = {(bf16_t)v.x, (bf16_t)v.y, (bf16_t)v.z, (bf16_t)v.w};  // round to nearest even
+  *reinterpret_cast<bf16x4*>(p) = r;
+}
+__device__ __forceinline__ float load1(const float* p) { return *p; }
+__device__ __forceinline__ float load1(const bf16_t* p) { return (float)*p; }
+__device__ __forceinline__ void store1(float* p, float v) { *p = v; }
+__device__ __forceinline__ void store1(bf16_t* p, float v) { *p = (bf16_t)v; }
+
+// value the stored state holds after rounding to its dtype (identity for fp32)
+template <typename ST> __device__ __forceinline__ float stored(float v) { return v; }
+template <> __device__ __forceinline__ float stored<bf16_t>(float v) { return (float)(bf16_t)v; }
+
+struct Coef {
+  float mu, beta, one_minus_beta, alpha;
+  int use_prev;
+};
+
+// One element of Alg. 1's elementwise lines.  Returns M_k; updates a (A_k) in place.
+__device__ __forceinline__ float mona_element(float g, float gp, float& a, float m, const Coef& c) {
+  float d = c.use_prev ? (g - gp) : 0.0f;            // D_k = G_k - G_{k-1}
+  a = c.beta * a + c.one_minus_beta * d;             // A_k = beta_a A_{k-1} + (1 - beta_a) D_k
+  float gt = g + c.alpha * a;                        // Gt_k = G_k + alpha A_k
+  return c.mu * m + gt;                              // M_k = mu M_{k-1} + Gt_k
+}
+
+__device__ __forceinline__ float block_sum(float v, float* red) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);   // within the wavefront
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) red[wave] = v;                            // then across wavefronts in LDS
+  __syncthreads();
+  float t = 0.0f;
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int w = 0; w < kEwThreads / 64; ++w) t += red[w];
+  }
+  return t;
+}
+
+template <typename GT, typename ST, typename XT>
+__global__ __launch_bounds__(kEwThreads) void state_update_kernel(
+    const MatStatic* __restrict__ stat, const MatDynamic* __restrict__ dyn,
+    const BlockWork* __restrict__ work, float* __restrict__ partials, Coef c) {
+  __shared__ float red[kEwThreads / 64];
+  const BlockWork bw = work[blockIdx.x];
+  const MatStatic ms = stat[bw.mat];
+  const GT* __restrict__ g = static_cast<const GT*>(dyn[bw.mat].g);
+  ST* __restrict__ gp = static_cast<ST*>(ms.g_prev);
+  ST* __restrict__ ac = static_cast<ST*>(ms.acc);
+  float* __restrict__ mo = ms.mom;
+  XT* __restrict__ x = static_cast<XT*>(ms.x);
+
+  const int total = ms.m * ms.n;
+  const int base = bw.chunk * kEwChunk;
+  const int count = min(kEwChunk, total - base);
+  const int n = ms.n, ldx = ms.ldx;
+  float ss = 0.0f;
+
+  if ((n & 3) == 0) {
+    // rows are a multiple of 4 elements: 4-element groups never straddle a row
+    constexpr int kIter = kEwChunk / (kEwThreads * 4);
+    constexpr int kBatch = 4;
+    static_assert(kIter % kBatch == 0, "chunk must be a multiple of the batch");
+    for (int it0 = 0; it0 < kIter; it0 += kBatch) {
+      f32x4 vg[kBatch], vp[kBatch], va[kBatch], vm[kBatch];
+      int idx[kBatch];
+#pragma unroll
+      for (int b = 0; b < kBatch; ++b) {
+        const int i = ((it0 + b) * kEwThreads + threadIdx.x) * 4;
+        idx[b] = (i < count) ? base + i : -1;
+        if (idx[b] >= 0) {
+          vg[b] = load4(g + idx[b]);
+          vp[b] = load4(gp + idx[b]);
+          va[b] = load4(ac + idx[b]);
+          vm[b] = load4(mo + idx[b]);
+        }
+      }
+#pragma unroll
+      for (int b = 0; b < kBatch; ++b) {
+        if (idx[b] >= 0) {
+          float a4[4] = {va[b].x, va[b].y, va[b].z, va[b].w};
+          const float g4[4] = {vg[b].x, vg[b].y, vg[b].z, vg[b].w};
+          const float p4[4] = {vp[b].x, vp[b].y, vp[b].z, vp[b].w};
+          const float m4[4] = {vm[b].x, vm[b].y, vm[b].z, vm[b].w};
+          float n4[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) n4[e] = mona_element(g4[e], p4[e], a4[e], m4[e], c);
+          const f32x4 a = {a4[0], a4[1], a4[2], a4[3]};
+          const f32x4 mnew = {n4[0], n4[1], n4[2], n4[3]};
+          ss += mnew.x * mnew.x + mnew.y * mnew.y + mnew.z * mnew.z + mnew.w * mnew.w;
+          store4(gp + idx[b], vg[b]);                 // G_{k-1} <- G_k
+          store4(ac + idx[b], a);
+          store4(mo + idx[b], mnew);
+          const int xo = (ldx == n) ? idx[b] : (idx[b] / n) * ldx + (idx[b] % n);
+          store4(x + xo, mnew);
+        }
+      }
+    }
+  } else {
+    for (int i = threadIdx.x; i < count; i += kEwThreads) {
+      const int id = base + i;
+      float a = load1(ac + id);
+      const float gv = load1(g + id);
+      const float mnew = mona_element(gv, load1(gp + id), a, mo[id], c);
+      ss += mnew * mnew;
+      store1(gp + id, gv);
+      store1(ac + id, a);
+      mo[id] = mnew;
+      store1(x + (id / n) * ldx + (id % n), mnew);
+    }
+  }
+  const float t = block_sum(ss, red);
+  if (threadIdx.x == 0) partials[blockIdx.x] = t;
+}
+
+// ||M||_F per matrix from the per-block partial sums, added in a fixed order in fp64 so the
+// result does not depend on scheduling.  One wavefront per matrix.
+__global__ __launch_bounds__(64) void norm_finalize_kernel(const MatStatic* __restrict__ stat,
+                                                           const float* __restrict__ partials,
+                                                           MatScale* __restrict__ scales, float eps) {
+  const int mat = blockIdx.x;
+  const int first = stat[mat].first_block, nb = stat[mat].num_blocks;
+  double s = 0.0;
+  for (int i = threadIdx.x; i < nb; i += 64) s += (double)partials[first + i];
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+  if (threadIdx.x == 0) {
+    const float norm = (float)sqrt(s);
+    const float den = norm + eps;
+    MatScale r;
+    r.norm = norm;
+    r.status = 0u;
+    const bool finite = (den == den) && (den <= 3.402823466e38f);
+    if (!finite) {
+      r.inv = 0.0f;
+      r.status = 2u;
+    } else if (den <= 0.0f) {
+      r.inv = 0.0f;
+      r.status = 1u;
+    } else {
+      r.inv = 1.0f / den;
+    }
+    r.inv2 = r.inv * r.inv;
+    scales[mat] = r;
+  }
+}
+
+// O = X_0 and the parameter update when no Newton-Schulz iteration is requested (T = 0),
+// W <- (1 - eta lambda) W - eta gamma O   (Eq. muon_update).
+template <typename WT, typename XT>
+__global__ __launch_bounds__(kEwThreads) void plain_update_kernel(
+    const MatStatic* __restrict__ stat, const MatDynamic* __restrict__ dyn,
+    const MatScale* __restrict__ scales, const BlockWork* __restrict__ work,
+    void* const* __restrict__ o_ptrs, float lr, float wd, float gamma_coeff, int store_o, int want_w_dtype) {
+  const BlockWork bw = work[blockIdx.x];
+  const MatStatic ms = stat[bw.mat];
+  if (ms.w_dtype != want_w_dtype) return;
+  const MatScale sc = scales[bw.mat];
+  if (sc.status & 2u) return;
+  WT* __restrict__ w = static_cast<WT*>(dyn[bw.mat].w);
+  const XT* __restrict__ x = static_cast<const XT*>(ms.x);
+  XT* __restrict__ o = static_cast<XT*>(o_ptrs[bw.mat]);
+  const int total = ms.m * ms.n;
+  const int base = bw.chunk * kEwChunk;
+  const int count = min(kEwChunk, total - base);
+  const float gamma = gamma_coeff * sqrtf((float)max(ms.m, ms.n));
+  const float keep = 1.0f - lr * wd, os = lr * gamma;
+  for (int i = threadIdx.x; i < count; i += kEwThreads) {
+    const int id = base + i;
+    const int xo = (id / ms.n) * ms.ldx + (id % ms.n);
+    const float ov = stored<XT>(sc.inv * (float)x[xo]);
+    if (store_o) o[xo] = (XT)ov;
+    store1(w + id, keep * load1(w + id) - os * ov);
+  }
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint4* __restrict__ p, size_t n16) {
+  const uint4 z = {0u, 0u, 0u, 0u};
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+    p[i] = z;
+}
+
+template <typename GT, typename ST, typename XT>
+hipError_t launch_su(const MatStatic* stat, const MatDynamic* dyn, const BlockWork* work, float* partials,
+                     int num_blocks, Coef c, hipStream_t s) {
+  hipLaunchKernelGGL((state_update_kernel<GT, ST, XT>), dim3(num_blocks), dim3(kEwThreads), 0, s, stat, dyn,
+                     work, partials, c);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// The gradient dtype may differ between matrices: the host orders the work table by gradient
+// dtype and launches each dtype's range of blocks separately.
+hipError_t launch_state_update(const MatStatic* stat, const MatDynamic* dyn, const BlockWork* work,
+                               float* partials, int num_blocks, int g_bf16, int state_bf16, int x_is_f32,
+                               float mu, float beta_a, float alpha, int use_prev, hipStream_t s) {
+  if (num_blocks <= 0) return hipSuccess;
+  Coef c;
+  c.mu = mu;
+  c.beta = beta_a;
+  c.one_minus_beta = 1.0f - beta_a;
+  c.alpha = alpha;
+  c.use_prev = use_prev;
+  const int key = (g_bf16 ? 4 : 0) | (state_bf16 ? 2 : 0) | (x_is_f32 ? 1 : 0);
+  switch (key) {
+    case 0: return launch_su<float, float, bf16_t>(stat, dyn, work, partials, num_blocks, c, s);
+    case 1: return launch_su<float, float, float>(stat, dyn, work, partials, num_blocks, c, s);
+    case 2: return launch_su<float, bf16_t, bf16_t>(stat, dyn, work, partials, num_blocks, c, s);
+    case 3: return launch_su<float, bf16_t, float>(stat, dyn, work, partials, num_blocks, c, s);
+    case 4: return launch_su<bf16_t, float, bf16_t>(stat, dyn, work, partials, num_blocks, c, s);
+    case 5: return launch_su<bf16_t, float, float>(stat, dyn, work, partials, num_blocks, c, s);
+    case 6: return launch_su<bf16_t, bf16_t, bf16_t>(stat, dyn, work, partials, num_blocks, c, s);
+    default: return launch_su<bf16_t, bf16_t, float>(stat, dyn, work, partials, num_blocks, c, s);
+  }
+}
+
+hipError_t launch_norm_finalize(const MatStatic* stat, const float* partials, MatScale* scales, int count,
+                                float eps, hipStream_t s) {
+  if (count <= 0) return hipSuccess;
+  hipLaunchKernelGGL(norm_finalize_kernel, dim3(count), dim3(64), 0, s, stat, partials, scales, eps);
+  return hipGetLastError();
+}
+
+hipError_t launch_plain_update(const MatStatic* stat, const MatDynamic* dyn, const MatScale* scales,
+                               const BlockWork* work, int num_blocks, int x_is_f32, void* const* o_ptrs,
+                               float lr, float wd, float gamma_coeff, int store_o, hipStream_t s) {
+  if (num_blocks <= 0) return hipSuccess;
+  // one launch per parameter dtype; blocks of the other dtype return at once
+  for (int wd_t = 0; wd_t < 2; ++wd_t) {
+    if (x_is_f32) {
+      if (wd_t == 0)
+        hipLaunchKernelGGL((plain_update_kernel<float, float>), dim3(num_blocks), dim3(kEwThreads), 0, s, stat,
+                           dyn, scales, work, o_ptrs, lr, wd, gamma_coeff, store_o, 0);
+      else
+        hipLaunchKernelGGL((plain_update_kernel<bf16_t, float>), dim3(num_blocks), dim3(kEwThreads), 0, s, stat,
+                           dyn, scales, work, o_ptrs, lr, wd, gamma_coeff, store_o, 1);
+    } else {
+      if (wd_t == 0)
+        hipLaunchKernelGGL((plain_update_kernel<float, bf16_t>), dim3(num_blocks), dim3(kEwThreads), 0, s, stat,
+                           dyn, scales, work, o_ptrs, lr, wd, gamma_coeff, store_o, 0);
+      else
+        hipLaunchKernelGGL((plain_update_kernel<bf16_t, bf16_t>), dim3(num_blocks), dim3(kEwThreads), 0, s,
+                           stat, dyn, scales, work, o_ptrs, lr, wd, gamma_coeff, store_o, 1);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
+  if (bytes == 0) return hipSuccess;
+  const size_t n16 = bytes / 16;   // the arena is carved in multiples of 256 bytes
+  const int blocks = (int)((n16 + 255) / 256 < 8192 ? (n16 + 255) / 256 : 8192);
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, s, static_cast<uint4*>(p), n16);
+  return hipGetLastError();
+}
+
+}  // namespace mona

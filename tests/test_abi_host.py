@@ -1,0 +1,109 @@
+"""Host-side checks of the C ABI that need no GPU: the shared library loads, exports every
+function include/mona.h declares, sizes arenas and rejects bad arguments before touching HIP."""
+import ctypes as C
+import os
+import re
+
+import pytest
+import torch
+
+from paper_2605_26842_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "mona.h")
+
+pytestmark = pytest.mark.skipif(not os.path.exists(B.LIB_PATH), reason="libmona.so not built")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mona_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_function():
+    lib = B.load_library()
+    names = declared_functions()
+    assert "mona_init_state" in names and "mona_step" in names
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in mona.h but not exported"
+    assert sorted(B.EXPORTED) == names
+    assert lib.mona_version().decode().startswith("libmona")
+
+
+def shapes(*mn, w=B.MONA_BF16, g=B.MONA_F32):
+    arr = (B.mona_matrix * len(mn))()
+    for i, (m, n) in enumerate(mn):
+        arr[i].m, arr[i].n, arr[i].w_dtype, arr[i].g_dtype = m, n, w, g
+    return arr
+
+
+def test_state_size_accounts_for_state_and_workspace():
+    one = B.mona_state_size(shapes((256, 512)), 1)
+    n = 256 * 512
+    # 3 fp32 state arrays + two bf16 working copies + two 256x256 bf16 squares, plus small tables
+    assert one >= n * 12 + 2 * n * 2 + 2 * 256 * 256 * 2
+    assert one < n * 12 + 2 * n * 2 + 2 * 256 * 256 * 2 + 64 * 1024
+    lite = B.mona_state_size(shapes((256, 512)), 1, B.mona_options(0, B.MONA_BF16))
+    assert one - lite == 2 * n * 2                      # G_prev and A stored in bf16
+    f32 = B.mona_state_size(shapes((256, 512)), 1, B.mona_options(1, B.MONA_F32))
+    assert f32 - one == 2 * n * 2 + 2 * 256 * 256 * 2   # fp32 working copies
+    # padding: 100 x 300 works on 128 x 384 copies
+    rag = B.mona_state_size(shapes((100, 300)), 1)
+    assert rag >= 100 * 300 * 12 + 2 * 128 * 384 * 2 + 2 * 128 * 128 * 2
+    # the large MoE layer of the benchmark: ~45 GB of state, ~60 GB in all
+    layer = shapes(*([(4096, 4096)] * 4 + [(4096, 1536)] * 256 + [(1536, 4096)] * 128))
+    total = B.mona_state_size(layer, 388)
+    elems = 4 * 4096 * 4096 + 384 * 4096 * 1536
+    assert elems * 12 < total < elems * 12 * 1.6
+
+
+def rc_of(fn, *args):
+    return fn(*args), B.load_library().mona_last_error().decode()
+
+
+def test_bad_arguments_are_rejected_on_the_host():
+    lib = B.load_library()
+    out = C.c_size_t(0)
+    rc, msg = rc_of(lib.mona_state_size, None, 1, None, C.byref(out))
+    assert rc == B.MONA_EINVAL and "NULL" in msg
+    rc, _ = rc_of(lib.mona_state_size, shapes((4, 4)), 0, None, C.byref(out))
+    assert rc == B.MONA_EINVAL
+    rc, msg = rc_of(lib.mona_state_size, shapes((0, 4)), 1, None, C.byref(out))
+    assert rc == B.MONA_EINVAL and ">= 1" in msg
+    rc, msg = rc_of(lib.mona_state_size, shapes((65536, 65536)), 1, None, C.byref(out))
+    assert rc == B.MONA_EINVAL and "2^31" in msg
+    rc, _ = rc_of(lib.mona_state_size, shapes((4, 4), w=7), 1, None, C.byref(out))
+    assert rc == B.MONA_EINVAL
+    rc, _ = rc_of(lib.mona_state_size, shapes((4, 4)), 1, C.byref(B.mona_options(2, 0)), C.byref(out))
+    assert rc == B.MONA_EINVAL
+    rc, _ = rc_of(lib.mona_state_size, shapes((4, 4)), 1, None, None)
+    assert rc == B.MONA_EINVAL
+    # init: argument errors are reported before any HIP call
+    handle = C.c_void_p(0)
+    rc, msg = rc_of(lib.mona_init_state, shapes((4, 4)), 1, None, None, 1 << 20, None, C.byref(handle))
+    assert rc == B.MONA_EINVAL and "arena" in msg
+    rc, msg = rc_of(lib.mona_init_state, shapes((4, 4)), 1, None, 0x1001, 1 << 20, None, C.byref(handle))
+    assert rc == B.MONA_EINVAL and "aligned" in msg
+    rc, msg = rc_of(lib.mona_init_state, shapes((256, 512)), 1, None, 0x10000, 1024, None, C.byref(handle))
+    assert rc == B.MONA_ENOMEM and "too small" in msg
+    assert handle.value in (None, 0)
+    # step / view / free on a NULL state
+    hp = B.mona_hparams()
+    assert lib.mona_step(None, shapes((4, 4)), 1, C.byref(hp), None) == B.MONA_EINVAL
+    assert lib.mona_state_view(None, 0, 0, None) == B.MONA_EINVAL
+    assert lib.mona_free_state(None) == B.MONA_OK
+    with pytest.raises(B.MonaError):
+        B.mona_state_size(shapes((0, 0)), 1)
+
+
+def test_binding_refuses_cpu_tensors_and_bad_layouts():
+    w = torch.zeros(4, 6)
+    with pytest.raises(RuntimeError, match="GPU"):
+        B.MonaOptimizer([w])
+    with pytest.raises(ValueError):
+        B.make_matrices([torch.zeros(4, 6).t()])
+    with pytest.raises(TypeError):
+        B.make_matrices([torch.zeros(4, 6, dtype=torch.float16)])
+    with pytest.raises(FileNotFoundError):
+        B.load_library("/nonexistent/libmona.so")
