@@ -37,6 +37,7 @@ int fail(int code, const char* fmt, ...) {
   } while (0)
 
 constexpr size_t kAlign = 256;
+constexpr int kSmallSideF32 = 64;
 size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a; }
 int round_up(int v, int a) { return (v + a - 1) / a * a; }
 
@@ -48,6 +49,8 @@ struct Group {
   int rows_pad = 0, cols_pad = 0;  // padded native shape of the working copies
   int p_pad = 0;             // padded short side
   int gran = 128;            // padding granularity (largest tile usable)
+  bool f32 = false;          // products of this group run in fp32 (else bf16 operands)
+  int esize = 2;             // bytes per element of this group's working copies
   std::vector<int> members;  // matrix indices
   size_t x_off[2] = {0, 0};  // byte offsets in the arena: ping-pong X buffers
   size_t s_off = 0, b_off = 0;
@@ -57,7 +60,6 @@ struct Group {
 
 struct Layout {
   int count = 0;
-  int esize = 2;             // bytes per element of the Newton-Schulz working precision
   int ssize = 4;             // bytes per element of the stored G_{k-1}, A
   std::vector<size_t> gprev_off, acc_off, mom_off;
   size_t state_begin = 0, state_bytes = 0;     // persistent {G_prev, A, M}
@@ -105,7 +107,6 @@ int check_opts(const mona_options* o, mona_options* out) {
 
 void build_layout(const mona_matrix* mats, int count, const mona_options& opt, Layout& L) {
   L.count = count;
-  L.esize = opt.ns_precision == 1 ? 4 : 2;
   L.ssize = opt.state_dtype == MONA_BF16 ? 2 : 4;
   size_t off = 0;
   // persistent state, contiguous: this block is what checkpoints carry
@@ -137,7 +138,11 @@ void build_layout(const mona_matrix* mats, int count, const mona_options& opt, L
       g.n = mats[i].n;
       g.tall = g.m > g.n;
       const int r128 = round_up(g.m, 128), c128 = round_up(g.n, 128);
-      g.gran = (opt.ns_precision == 0 && r128 % 256 == 0 && c128 % 256 == 0) ? 256 : 128;
+      // bf16 rounding errors of the p x p Gram entries average out over p singular directions;
+      // below p = 64 they do not, and the products cost nothing there, so they run in fp32
+      g.f32 = opt.ns_precision == 1 || std::min(g.m, g.n) <= kSmallSideF32;
+      g.esize = g.f32 ? 4 : 2;
+      g.gran = (!g.f32 && r128 % 256 == 0 && c128 % 256 == 0) ? 256 : 128;
       g.rows_pad = r128;
       g.cols_pad = c128;
       g.p_pad = g.tall ? g.cols_pad : g.rows_pad;
@@ -154,9 +159,9 @@ void build_layout(const mona_matrix* mats, int count, const mona_options& opt, L
     const size_t cnt = g.members.size();
     g.x_stride = (int64_t)g.rows_pad * g.cols_pad;
     g.s_stride = (int64_t)g.p_pad * g.p_pad;
-    for (int b = 0; b < 2; ++b) { g.x_off[b] = off; off = align_up(off + cnt * g.x_stride * L.esize); }
-    g.s_off = off; off = align_up(off + cnt * g.s_stride * L.esize);
-    g.b_off = off; off = align_up(off + cnt * g.s_stride * L.esize);
+    for (int b = 0; b < 2; ++b) { g.x_off[b] = off; off = align_up(off + cnt * g.x_stride * g.esize); }
+    g.s_off = off; off = align_up(off + cnt * g.s_stride * g.esize);
+    g.b_off = off; off = align_up(off + cnt * g.s_stride * g.esize);
   }
   L.work_bytes = off - L.work_begin;
 
@@ -227,8 +232,8 @@ struct mona_state {
 namespace {
 
 // tile used by one product of a group
-int pick_tile(const Group& g, int kind, int count, bool f32) {
-  if (f32 || g.gran < 256) return 128;
+int pick_tile(const Group& g, int kind, int count) {
+  if (g.f32 || g.gran < 256) return 128;
   long long tiles;
   if (kind == OP_APPLY) {
     tiles = (long long)(g.rows_pad / 256) * (g.cols_pad / 256) * count;
@@ -421,7 +426,7 @@ int mona_init_state(const mona_matrix* mats, int32_t count, const mona_options* 
     ms.g_prev = st->arena + L.gprev_off[i];
     ms.acc = st->arena + L.acc_off[i];
     ms.mom = reinterpret_cast<float*>(st->arena + L.mom_off[i]);
-    ms.x = st->arena + g.x_off[0] + (size_t)L.rank_in_group[i] * g.x_stride * L.esize;
+    ms.x = st->arena + g.x_off[0] + (size_t)L.rank_in_group[i] * g.x_stride * g.esize;
     ms.m = mats[i].m;
     ms.n = mats[i].n;
     ms.ldx = g.cols_pad;
@@ -429,7 +434,8 @@ int mona_init_state(const mona_matrix* mats, int32_t count, const mona_options* 
     ms.g_dtype = mats[i].g_dtype;
     ms.first_block = L.first_block[i];
     ms.num_blocks = L.num_blocks[i];
-    optr[i] = st->arena + g.x_off[1] + (size_t)L.rank_in_group[i] * g.x_stride * L.esize;
+    ms.x_f32 = g.f32 ? 1 : 0;
+    optr[i] = st->arena + g.x_off[1] + (size_t)L.rank_in_group[i] * g.x_stride * g.esize;
   }
   INIT_TRY(hipMemcpyAsync(st->arena + L.stat_off, stat.data(), sizeof(MatStatic) * count, hipMemcpyHostToDevice, s));
   INIT_TRY(hipMemcpyAsync(st->arena + L.optr_off, optr.data(), sizeof(void*) * count, hipMemcpyHostToDevice, s));
@@ -463,7 +469,6 @@ int mona_step(mona_state* st, const mona_matrix* mats, int32_t count, const mona
                   b.n);
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const bool f32 = st->opt.ns_precision == 1;
 
   // per-step pointer table
   bool changed = !st->dyn_valid;
@@ -503,10 +508,10 @@ int mona_step(mona_state* st, const mona_matrix* mats, int32_t count, const mona
   // Alg. 1: difference, acceleration EMA, accelerated gradient, momentum, roll; sum of squares
   const int use_prev = !((hp->flags & MONA_FLAG_FIRST_DIFF_ZERO) && st->k == 0);
   const int sbf = st->opt.state_dtype == MONA_BF16;
-  HIP_TRY(launch_state_update(stat, dyn, blocks, partials, L.blocks_f32g, 0, sbf, f32, hp->momentum, hp->beta_a,
+  HIP_TRY(launch_state_update(stat, dyn, blocks, partials, L.blocks_f32g, 0, sbf, hp->momentum, hp->beta_a,
                               hp->alpha, use_prev, s));
   HIP_TRY(launch_state_update(stat, dyn, blocks + L.blocks_f32g, partials + L.blocks_f32g, nblocks - L.blocks_f32g, 1,
-                              sbf, f32, hp->momentum, hp->beta_a, hp->alpha, use_prev, s));
+                              sbf, hp->momentum, hp->beta_a, hp->alpha, use_prev, s));
   HIP_TRY(launch_norm_finalize(stat, partials, scales, count, hp->ns_eps, s));
   if (prof) HIP_TRY(hipEventRecord(st->ev[1], s));
 
@@ -522,7 +527,7 @@ int mona_step(mona_state* st, const mona_matrix* mats, int32_t count, const mona
       for (int kind = OP_GRAM; kind <= OP_APPLY; ++kind) {
         GemmArgs a;
         bool tp = false, tq = false;
-        const int tile = pick_tile(g, kind, cnt, f32);
+        const int tile = pick_tile(g, kind, cnt);
         fill_gemm(st, g, kind, tile, src, *hp, t == 0, t == T - 1, a, tp, tq);
         LaunchRecord rec;
         const bool each = st->profiling > 1;
@@ -530,7 +535,7 @@ int mona_step(mona_state* st, const mona_matrix* mats, int32_t count, const mona
           if (!get_event_pair(st, &rec.e0, &rec.e1)) return fail(MONA_EHIP, "hipEventCreate failed");
           HIP_TRY(hipEventRecord(rec.e0, s));
         }
-        HIP_TRY(launch_ns_gemm(a, tile, tp, tq, f32, s));
+        HIP_TRY(launch_ns_gemm(a, tile, tp, tq, g.f32, s));
         if (each) {
           HIP_TRY(hipEventRecord(rec.e1, s));
           rec.kind = kind; rec.group = (int)gi; rec.iter = t; rec.tile = tile;
@@ -544,7 +549,7 @@ int mona_step(mona_state* st, const mona_matrix* mats, int32_t count, const mona
   if (prof) HIP_TRY(hipEventRecord(st->ev[2], s));
   if (T == 0) {
     // O = X_0, then Eq. muon_update
-    HIP_TRY(launch_plain_update(stat, dyn, scales, blocks, nblocks, f32, st->at<void*>(L.optr_off), hp->lr,
+    HIP_TRY(launch_plain_update(stat, dyn, scales, blocks, nblocks, st->at<void*>(L.optr_off), hp->lr,
                                 hp->weight_decay, hp->gamma_coeff, (hp->flags & MONA_FLAG_KEEP_O) ? 1 : 0, s));
   }
   if (prof) {
@@ -585,9 +590,9 @@ int mona_state_view(mona_state* st, int32_t i, int32_t kind, mona_view* out) {
     case MONA_VIEW_O: {
       // iteration t reads buffer t % 2 and writes the other one; with T = 0 the update kernel
       // writes buffer 1
-      out->ptr = st->arena + g.x_off[st->o_buf] + (size_t)L.rank_in_group[i] * g.x_stride * L.esize;
+      out->ptr = st->arena + g.x_off[st->o_buf] + (size_t)L.rank_in_group[i] * g.x_stride * g.esize;
       out->ld = g.cols_pad;
-      out->dtype = st->opt.ns_precision == 1 ? MONA_F32 : MONA_BF16;
+      out->dtype = g.f32 ? MONA_F32 : MONA_BF16;
       break;
     }
     default: return fail(MONA_EINVAL, "unknown view kind %d", kind);
@@ -679,7 +684,6 @@ int mona_plan_info(mona_state* st, int32_t ns_steps, int64_t* launches_out, doub
   if (!st) return fail(MONA_EINVAL, "state is NULL");
   if (ns_steps < 0) return fail(MONA_EINVAL, "ns_steps must be >= 0");
   const Layout& L = st->L;
-  const bool f32 = st->opt.ns_precision == 1;
   mona_hparams hp;
   memset(&hp, 0, sizeof hp);
   double flops = 0.0;
@@ -689,7 +693,7 @@ int mona_plan_info(mona_state* st, int32_t ns_steps, int64_t* launches_out, doub
     for (int kind = OP_GRAM; kind <= OP_APPLY; ++kind) {
       GemmArgs a;
       bool tp, tq;
-      const int tile = pick_tile(g, kind, cnt, f32);
+      const int tile = pick_tile(g, kind, cnt);
       fill_gemm(st, g, kind, tile, 0, hp, false, false, a, tp, tq);
       flops += gemm_flops(a, tile) * ns_steps;
       launches += ns_steps;
@@ -700,7 +704,7 @@ int mona_plan_info(mona_state* st, int32_t ns_steps, int64_t* launches_out, doub
     const double ne = (double)st->mats[i].m * st->mats[i].n;
     const double gsz = st->mats[i].g_dtype == MONA_BF16 ? 2 : 4;
     // state pass: read G, G_prev, A, M; write G_prev, A, M and the working copy of M
-    bytes += ne * (gsz + 2 * L.ssize + 4 + 2 * L.ssize + 4 + L.esize);
+    bytes += ne * (gsz + 2 * L.ssize + 4 + 2 * L.ssize + 4 + L.groups[L.group_of[i]].esize);
   }
   if (launches_out) *launches_out = launches;
   if (ns_flops_executed_out) *ns_flops_executed_out = flops;

@@ -19,7 +19,7 @@ struct MatStatic {
   int32_t w_dtype, g_dtype;
   int32_t first_block; // first block of the elementwise grid that belongs to this matrix
   int32_t num_blocks;  // number of such blocks
-  int32_t pad;
+  int32_t x_f32;       // 1: x (and the whole Newton-Schulz workspace of this matrix) is fp32, else bf16
 };
 
 // Per-step pointers (the caller may pass fresh buffers every step).
@@ -78,13 +78,13 @@ struct GemmArgs {
 
 // kernels (defined in the .hip files)
 hipError_t launch_state_update(const MatStatic* stat, const MatDynamic* dyn, const BlockWork* work,
-                               float* partials, int num_blocks, int g_bf16, int state_bf16, int x_is_f32,
-                               float mu, float beta_a, float alpha, int use_prev, hipStream_t s);
+                               float* partials, int num_blocks, int g_bf16, int state_bf16, float mu,
+                               float beta_a, float alpha, int use_prev, hipStream_t s);
 hipError_t launch_norm_finalize(const MatStatic* stat, const float* partials, MatScale* scales,
                                 int count, float eps, hipStream_t s);
 hipError_t launch_plain_update(const MatStatic* stat, const MatDynamic* dyn, const MatScale* scales,
-                               const BlockWork* work, int num_blocks, int x_is_f32, void* const* o_ptrs,
-                               float lr, float wd, float gamma_coeff, int store_o, hipStream_t s);
+                               const BlockWork* work, int num_blocks, void* const* o_ptrs, float lr, float wd,
+                               float gamma_coeff, int store_o, hipStream_t s);
 hipError_t launch_ns_gemm(const GemmArgs& a, int tile, bool transP, bool transQ, bool f32,
                           hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);

@@ -61,7 +61,7 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   return t;
 }
 
-template <typename GT, typename ST, typename XT>
+template <typename GT, typename ST>
 __global__ __launch_bounds__(kEwThreads) void state_update_kernel(
     const MatStatic* __restrict__ stat, const MatDynamic* __restrict__ dyn,
     const BlockWork* __restrict__ work, float* __restrict__ partials, Coef c) {
@@ -72,7 +72,10 @@ __global__ __launch_bounds__(kEwThreads) void state_update_kernel(
   ST* __restrict__ gp = static_cast<ST*>(ms.g_prev);
   ST* __restrict__ ac = static_cast<ST*>(ms.acc);
   float* __restrict__ mo = ms.mom;
-  XT* __restrict__ x = static_cast<XT*>(ms.x);
+  // working copy of M_k for the matrix products: bf16, or fp32 for matrices orthogonalised in fp32
+  bf16_t* __restrict__ xh = static_cast<bf16_t*>(ms.x);
+  float* __restrict__ xf = static_cast<float*>(ms.x);
+  const bool xf32 = ms.x_f32 != 0;
 
   const int total = ms.m * ms.n;
   const int base = bw.chunk * kEwChunk;
@@ -116,7 +119,7 @@ __global__ __launch_bounds__(kEwThreads) void state_update_kernel(
           store4(ac + idx[b], a);
           store4(mo + idx[b], mnew);
           const int xo = (ldx == n) ? idx[b] : (idx[b] / n) * ldx + (idx[b] % n);
-          store4(x + xo, mnew);
+          if (xf32) store4(xf + xo, mnew); else store4(xh + xo, mnew);
         }
       }
     }
@@ -130,7 +133,8 @@ __global__ __launch_bounds__(kEwThreads) void state_update_kernel(
       store1(gp + id, gv);
       store1(ac + id, a);
       mo[id] = mnew;
-      store1(x + (id / n) * ldx + (id % n), mnew);
+      const int xo = (id / n) * ldx + (id % n);
+      if (xf32) xf[xo] = mnew; else xh[xo] = (bf16_t)mnew;
     }
   }
   const float t = block_sum(ss, red);
@@ -171,7 +175,7 @@ __global__ __launch_bounds__(64) void norm_finalize_kernel(const MatStatic* __re
 
 // O = X_0 and the parameter update when no Newton-Schulz iteration is requested (T = 0),
 // W <- (1 - eta lambda) W - eta gamma O   (Eq. muon_update).
-template <typename WT, typename XT>
+template <typename WT>
 __global__ __launch_bounds__(kEwThreads) void plain_update_kernel(
     const MatStatic* __restrict__ stat, const MatDynamic* __restrict__ dyn,
     const MatScale* __restrict__ scales, const BlockWork* __restrict__ work,
@@ -182,8 +186,11 @@ __global__ __launch_bounds__(kEwThreads) void plain_update_kernel(
   const MatScale sc = scales[bw.mat];
   if (sc.status & 2u) return;
   WT* __restrict__ w = static_cast<WT*>(dyn[bw.mat].w);
-  const XT* __restrict__ x = static_cast<const XT*>(ms.x);
-  XT* __restrict__ o = static_cast<XT*>(o_ptrs[bw.mat]);
+  const bool xf32 = ms.x_f32 != 0;
+  const bf16_t* __restrict__ xh = static_cast<const bf16_t*>(ms.x);
+  const float* __restrict__ xf = static_cast<const float*>(ms.x);
+  bf16_t* __restrict__ oh = static_cast<bf16_t*>(o_ptrs[bw.mat]);
+  float* __restrict__ of = static_cast<float*>(o_ptrs[bw.mat]);
   const int total = ms.m * ms.n;
   const int base = bw.chunk * kEwChunk;
   const int count = min(kEwChunk, total - base);
@@ -192,8 +199,11 @@ __global__ __launch_bounds__(kEwThreads) void plain_update_kernel(
   for (int i = threadIdx.x; i < count; i += kEwThreads) {
     const int id = base + i;
     const int xo = (id / ms.n) * ms.ldx + (id % ms.n);
-    const float ov = stored<XT>(sc.inv * (float)x[xo]);
-    if (store_o) o[xo] = (XT)ov;
+    // O = X_0 in the working precision of this matrix
+    const float ov = xf32 ? sc.inv * xf[xo] : stored<bf16_t>(sc.inv * (float)xh[xo]);
+    if (store_o) {
+      if (xf32) of[xo] = ov; else oh[xo] = (bf16_t)ov;
+    }
     store1(w + id, keep * load1(w + id) - os * ov);
   }
 }
@@ -204,10 +214,10 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(uint4* __restrict__ p, s
     p[i] = z;
 }
 
-template <typename GT, typename ST, typename XT>
+template <typename GT, typename ST>
 hipError_t launch_su(const MatStatic* stat, const MatDynamic* dyn, const BlockWork* work, float* partials,
                      int num_blocks, Coef c, hipStream_t s) {
-  hipLaunchKernelGGL((state_update_kernel<GT, ST, XT>), dim3(num_blocks), dim3(kEwThreads), 0, s, stat, dyn,
+  hipLaunchKernelGGL((state_update_kernel<GT, ST>), dim3(num_blocks), dim3(kEwThreads), 0, s, stat, dyn,
                      work, partials, c);
   return hipGetLastError();
 }
@@ -217,8 +227,8 @@ hipError_t launch_su(const MatStatic* stat, const MatDynamic* dyn, const BlockWo
 // The gradient dtype may differ between matrices: the host orders the work table by gradient
 // dtype and launches each dtype's range of blocks separately.
 hipError_t launch_state_update(const MatStatic* stat, const MatDynamic* dyn, const BlockWork* work,
-                               float* partials, int num_blocks, int g_bf16, int state_bf16, int x_is_f32,
-                               float mu, float beta_a, float alpha, int use_prev, hipStream_t s) {
+                               float* partials, int num_blocks, int g_bf16, int state_bf16, float mu,
+                               float beta_a, float alpha, int use_prev, hipStream_t s) {
   if (num_blocks <= 0) return hipSuccess;
   Coef c;
   c.mu = mu;
@@ -226,16 +236,12 @@ hipError_t launch_state_update(const MatStatic* stat, const MatDynamic* dyn, con
   c.one_minus_beta = 1.0f - beta_a;
   c.alpha = alpha;
   c.use_prev = use_prev;
-  const int key = (g_bf16 ? 4 : 0) | (state_bf16 ? 2 : 0) | (x_is_f32 ? 1 : 0);
+  const int key = (g_bf16 ? 2 : 0) | (state_bf16 ? 1 : 0);
   switch (key) {
-    case 0: return launch_su<float, float, bf16_t>(stat, dyn, work, partials, num_blocks, c, s);
-    case 1: return launch_su<float, float, float>(stat, dyn, work, partials, num_blocks, c, s);
-    case 2: return launch_su<float, bf16_t, bf16_t>(stat, dyn, work, partials, num_blocks, c, s);
-    case 3: return launch_su<float, bf16_t, float>(stat, dyn, work, partials, num_blocks, c, s);
-    case 4: return launch_su<bf16_t, float, bf16_t>(stat, dyn, work, partials, num_blocks, c, s);
-    case 5: return launch_su<bf16_t, float, float>(stat, dyn, work, partials, num_blocks, c, s);
-    case 6: return launch_su<bf16_t, bf16_t, bf16_t>(stat, dyn, work, partials, num_blocks, c, s);
-    default: return launch_su<bf16_t, bf16_t, float>(stat, dyn, work, partials, num_blocks, c, s);
+    case 0: return launch_su<float, float>(stat, dyn, work, partials, num_blocks, c, s);
+    case 1: return launch_su<float, bf16_t>(stat, dyn, work, partials, num_blocks, c, s);
+    case 2: return launch_su<bf16_t, float>(stat, dyn, work, partials, num_blocks, c, s);
+    default: return launch_su<bf16_t, bf16_t>(stat, dyn, work, partials, num_blocks, c, s);
   }
 }
 
@@ -247,30 +253,17 @@ hipError_t launch_norm_finalize(const MatStatic* stat, const float* partials, Ma
 }
 
 hipError_t launch_plain_update(const MatStatic* stat, const MatDynamic* dyn, const MatScale* scales,
-                               const BlockWork* work, int num_blocks, int x_is_f32, void* const* o_ptrs,
-                               float lr, float wd, float gamma_coeff, int store_o, hipStream_t s) {
+                               const BlockWork* work, int num_blocks, void* const* o_ptrs, float lr, float wd,
+                               float gamma_coeff, int store_o, hipStream_t s) {
   if (num_blocks <= 0) return hipSuccess;
   // one launch per parameter dtype; blocks of the other dtype return at once
-  for (int wd_t = 0; wd_t < 2; ++wd_t) {
-    if (x_is_f32) {
-      if (wd_t == 0)
-        hipLaunchKernelGGL((plain_update_kernel<float, float>), dim3(num_blocks), dim3(kEwThreads), 0, s, stat,
-                           dyn, scales, work, o_ptrs, lr, wd, gamma_coeff, store_o, 0);
-      else
-        hipLaunchKernelGGL((plain_update_kernel<bf16_t, float>), dim3(num_blocks), dim3(kEwThreads), 0, s, stat,
-                           dyn, scales, work, o_ptrs, lr, wd, gamma_coeff, store_o, 1);
-    } else {
-      if (wd_t == 0)
-        hipLaunchKernelGGL((plain_update_kernel<float, bf16_t>), dim3(num_blocks), dim3(kEwThreads), 0, s, stat,
-                           dyn, scales, work, o_ptrs, lr, wd, gamma_coeff, store_o, 0);
-      else
-        hipLaunchKernelGGL((plain_update_kernel<bf16_t, bf16_t>), dim3(num_blocks), dim3(kEwThreads), 0, s,
-                           stat, dyn, scales, work, o_ptrs, lr, wd, gamma_coeff, store_o, 1);
-    }
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
-  return hipSuccess;
+  hipLaunchKernelGGL((plain_update_kernel<float>), dim3(num_blocks), dim3(kEwThreads), 0, s, stat, dyn, scales,
+                     work, o_ptrs, lr, wd, gamma_coeff, store_o, 0);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((plain_update_kernel<bf16_t>), dim3(num_blocks), dim3(kEwThreads), 0, s, stat, dyn, scales,
+                     work, o_ptrs, lr, wd, gamma_coeff, store_o, 1);
+  return hipGetLastError();
 }
 
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {

@@ -59,7 +59,8 @@ def run_gpu(weights: Sequence[torch.Tensor], grads_per_step, hp: wl.HParams, ns_
     """Run len(grads_per_step) steps through the C ABI.  Returns (optimizer, device weights,
     history) with history[k][i] a Snapshot for every watched matrix i."""
     dev_w = [w.to(device).contiguous() for w in weights]
-    opt = B.MonaOptimizer(dev_w, ns_precision=ns_precision, state_dtype=state_dtype)
+    opt = B.MonaOptimizer(dev_w, ns_precision=ns_precision, state_dtype=state_dtype,
+                          g_dtype=grads_per_step[0][0].dtype)
     watch = list(range(len(weights))) if watch is None else list(watch)
     hp = dataclasses.replace(hp, flags=hp.flags | B.MONA_FLAG_KEEP_O)
     history = []
