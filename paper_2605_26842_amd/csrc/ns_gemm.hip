@@ -170,59 +170,143 @@ __device__ __forceinline__ float to_f32(bf16_t v) { return (float)v; }
 __device__ __forceinline__ float to_f32(float v) { return v; }
 
 // ---- epilogue -----------------------------------------------------------------------------
-// acc[v] of a 32x32 MFMA block: row = (v / 4) * 8 + (lane / 32) * 4 + (v % 4), col = lane % 32.
-template <typename T>
-__device__ __forceinline__ void epilogue_block(const GemmArgs& a, const f32x16& acc, int mat, int row0,
-                                               int col0, bool mirror, float post, const T* __restrict__ E,
-                                               T* __restrict__ C, const MatStatic* ms, void* wptr,
-                                               bool skip_w) {
-  const int lane = threadIdx.x & 63;
-  const int col = col0 + (lane & 31);
-  const int rbase = row0 + (lane >> 5) * 4;
+// The accumulators of a wavefront (MI x NI blocks of 32 x 32; acc[v] of a block sits at
+// row = (v / 4) * 8 + (lane / 32) * 4 + (v % 4), col = lane % 32) are staged through LDS one
+// 32-row band at a time, so that every global access of the epilogue is a 16-byte vector that
+// runs along a row:  out = post * (beta * E + alpha * acc), then either a plain store (plus the
+// mirrored store of a symmetric product) or the parameter update of Eq. muon_update.
+template <typename T> struct Chunk;           // 16 bytes of T
+template <> struct Chunk<bf16_t> { static constexpr int N = 8; typedef bf16x8 vec; };
+template <> struct Chunk<float> { static constexpr int N = 4; typedef f32x4 vec; };
+
+template <typename T, int WN, int MI, int NI>
+__device__ __forceinline__ void tile_epilogue(const GemmArgs& a, f32x16 (&acc)[MI][NI], float* __restrict__ lds_f,
+                                              int tmat, int row_w0, int col_w0, bool mirror) {
+  constexpr int CH = Chunk<T>::N;
+  typedef typename Chunk<T>::vec vec_t;
+  constexpr int LDW = WN + 4;                    // floats per staged row (+4: the two half-waves
+                                                 // write rows 4 apart, keep them on different banks)
+  constexpr int CPR = WN / CH;                   // chunks per row
+  constexpr int PASSES = 32 * CPR / 64;          // chunks per lane per band
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float* __restrict__ stage = lds_f + wave * (32 * LDW);
+
+  const int mi = a.members ? a.members[tmat] : tmat;
+  float post = 1.0f;
+  if (a.post == POST_INV) post = a.scales[mi].inv;
+  else if (a.post == POST_INV2) post = a.scales[mi].inv2;
+  const T* __restrict__ E = a.E ? static_cast<const T*>(a.E) + (size_t)tmat * a.strideE : nullptr;
+  T* __restrict__ C = static_cast<T*>(a.C) + (size_t)tmat * a.strideC;
+  const bool update = a.epilogue == EPI_UPDATE;
+  int wm_real = 0, wn_real = 0, w_is_bf16 = 0;
+  bool skip_w = true;
+  void* wptr = nullptr;
+  if (update) {
+    const MatStatic& ms = a.stat[mi];
+    wm_real = ms.m; wn_real = ms.n; w_is_bf16 = ms.w_dtype;
+    wptr = a.dyn[mi].w;
+    skip_w = (a.scales[mi].status & 2u) != 0;
+  }
+  const bool w_vec_ok = (wn_real % CH) == 0;
+
+  static_for<MI>([&](auto i) {
+    __syncthreads();     // previous band fully consumed (first band: operand tiles no longer read)
+    static_for<NI>([&](auto j) {
 #pragma unroll
-  for (int vg = 0; vg < 4; ++vg) {
-    float o[4];
+      for (int v = 0; v < 16; ++v) {
+        const int r = (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+        stage[r * LDW + j * 32 + (lane & 31)] = acc[i][j][v];
+      }
+    });
+    __syncthreads();
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int row = rbase + vg * 8 + e;
-      float val = a.alpha * acc[vg * 4 + e];
-      if (E != nullptr) val += a.beta * to_f32(E[(size_t)row * a.lde + col]);
-      o[e] = post * val;
-    }
-    if (a.epilogue == EPI_STORE) {
+    for (int pss = 0; pss < PASSES; ++pss) {
+      const int idx = pss * 64 + lane;
+      const int r = idx / CPR, ch = idx % CPR;
+      const int grow = row_w0 + i * 32 + r, gcol = col_w0 + ch * CH;
+      float val[CH];
+      {
+        const f32x4* src = reinterpret_cast<const f32x4*>(stage + r * LDW + ch * CH);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) C[(size_t)(rbase + vg * 8 + e) * a.ldc + col] = (T)o[e];
-      if (mirror) {
-        // the transposed tile: 4 consecutive rows of this lane become 4 consecutive columns
-        T* dst = C + (size_t)col * a.ldc + rbase + vg * 8;
-        if constexpr (sizeof(T) == 2) {
-          bf16x4 pk = {(bf16_t)o[0], (bf16_t)o[1], (bf16_t)o[2], (bf16_t)o[3]};
-          *reinterpret_cast<bf16x4*>(dst) = pk;
-        } else {
-          f32x4 pk = {o[0], o[1], o[2], o[3]};
-          *reinterpret_cast<f32x4*>(dst) = pk;
+        for (int q = 0; q < CH / 4; ++q) {
+          const f32x4 t4 = src[q];
+          val[q * 4 + 0] = t4.x; val[q * 4 + 1] = t4.y; val[q * 4 + 2] = t4.z; val[q * 4 + 3] = t4.w;
         }
       }
-    } else {
-      // O_k = out; W <- (1 - eta lambda) W - eta gamma O   (Eq. muon_update), inside the real m x n
+      if (E != nullptr) {
+        const vec_t ev = *reinterpret_cast<const vec_t*>(E + (size_t)grow * a.lde + gcol);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int row = rbase + vg * 8 + e;
-        const float ov = to_f32((T)o[e]);     // O_k as stored in the working precision
-        if (a.store_out) C[(size_t)row * a.ldc + col] = (T)ov;
-        if (!skip_w && row < ms->m && col < ms->n) {
-          const size_t wi = (size_t)row * ms->n + col;
-          if (ms->w_dtype == 1) {
-            bf16_t* w = static_cast<bf16_t*>(wptr);
-            w[wi] = (bf16_t)(a.w_keep * (float)w[wi] - a.o_scale * ov);
+        for (int e = 0; e < CH; ++e) val[e] = post * (a.alpha * val[e] + a.beta * to_f32(ev[e]));
+      } else {
+#pragma unroll
+        for (int e = 0; e < CH; ++e) val[e] = post * (a.alpha * val[e]);
+      }
+      vec_t ov;
+#pragma unroll
+      for (int e = 0; e < CH; ++e) ov[e] = (T)val[e];
+      if (!update || a.store_out) *reinterpret_cast<vec_t*>(C + (size_t)grow * a.ldc + gcol) = ov;
+      if (mirror) {
+        // keep the rounded result for the transposed store below
+        f32x4* dst = reinterpret_cast<f32x4*>(stage + r * LDW + ch * CH);
+#pragma unroll
+        for (int q = 0; q < CH / 4; ++q) {
+          f32x4 t4 = {to_f32(ov[q * 4 + 0]), to_f32(ov[q * 4 + 1]), to_f32(ov[q * 4 + 2]), to_f32(ov[q * 4 + 3])};
+          dst[q] = t4;
+        }
+      }
+      if (update && !skip_w && grow < wm_real) {
+        // W <- (1 - eta lambda) W - eta gamma O, O as stored in the working precision
+        const size_t wi = (size_t)grow * wn_real + gcol;
+        if (w_vec_ok && gcol + CH <= wn_real) {
+          if (w_is_bf16) {
+            typedef bf16_t wv_t __attribute__((ext_vector_type(CH)));
+            wv_t* wp = reinterpret_cast<wv_t*>(static_cast<bf16_t*>(wptr) + wi);
+            wv_t wv = *wp;
+#pragma unroll
+            for (int e = 0; e < CH; ++e) wv[e] = (bf16_t)(a.w_keep * (float)wv[e] - a.o_scale * to_f32(ov[e]));
+            *wp = wv;
           } else {
-            float* w = static_cast<float*>(wptr);
-            w[wi] = a.w_keep * w[wi] - a.o_scale * ov;
+            f32x4* wp = reinterpret_cast<f32x4*>(static_cast<float*>(wptr) + wi);
+#pragma unroll
+            for (int q = 0; q < CH / 4; ++q) {
+              f32x4 wv = wp[q];
+#pragma unroll
+              for (int e = 0; e < 4; ++e) wv[e] = a.w_keep * wv[e] - a.o_scale * to_f32(ov[q * 4 + e]);
+              wp[q] = wv;
+            }
+          }
+        } else {
+#pragma unroll
+          for (int e = 0; e < CH; ++e) {
+            if (gcol + e < wn_real) {
+              if (w_is_bf16) {
+                bf16_t* w = static_cast<bf16_t*>(wptr) + wi + e;
+                *w = (bf16_t)(a.w_keep * (float)*w - a.o_scale * to_f32(ov[e]));
+              } else {
+                float* w = static_cast<float*>(wptr) + wi + e;
+                *w = a.w_keep * *w - a.o_scale * to_f32(ov[e]);
+              }
+            }
           }
         }
       }
     }
-  }
+    if (mirror) {
+      // transposed copy of this band: C[col][row], 16-byte pieces along the band's 32 rows
+      __syncthreads();
+      constexpr int RCH = 32 / CH;               // row-chunks per band
+      constexpr int MPASSES = WN * RCH / 64;
+#pragma unroll
+      for (int pss = 0; pss < MPASSES; ++pss) {
+        const int idx = pss * 64 + lane;
+        const int c = idx % WN, rc = idx / WN;
+        vec_t ov;
+#pragma unroll
+        for (int e = 0; e < CH; ++e) ov[e] = (T)stage[(rc * CH + e) * LDW + c];
+        *reinterpret_cast<vec_t*>(C + (size_t)(col_w0 + c) * a.ldc + row_w0 + i * 32 + rc * CH) = ov;
+      }
+    }
+  });
 }
 
 // ---- bf16 kernel -----------------------------------------------------------------------------
@@ -296,28 +380,9 @@ __global__ __launch_bounds__(kThreads) void ns_gemm_bf16_kernel(const GemmArgs a
     __syncthreads();
   }
 
-  // epilogue
-  const int mi = a.members ? a.members[t.mat] : t.mat;
-  float post = 1.0f;
-  if (a.post == POST_INV) post = a.scales[mi].inv;
-  else if (a.post == POST_INV2) post = a.scales[mi].inv2;
-  const bf16_t* E = a.E ? static_cast<const bf16_t*>(a.E) + (size_t)t.mat * a.strideE : nullptr;
-  bf16_t* C = static_cast<bf16_t*>(a.C) + (size_t)t.mat * a.strideC;
-  const MatStatic* ms = nullptr;
-  void* wptr = nullptr;
-  bool skip_w = false;
-  if (a.epilogue == EPI_UPDATE) {
-    ms = a.stat + mi;
-    wptr = a.dyn[mi].w;
-    skip_w = (a.scales[mi].status & 2u) != 0;
-  }
   const bool mirror = a.symmetric && (t.ti != t.tj);
-  static_for<MI>([&](auto i) {
-    static_for<NI>([&](auto j) {
-      epilogue_block<bf16_t>(a, acc[i][j], t.mat, m0 + wm * WM + i * 32, n0 + wn * WN + j * 32, mirror, post, E,
-                             C, ms, wptr, skip_w);
-    });
-  });
+  tile_epilogue<bf16_t, WN, MI, NI>(a, acc, reinterpret_cast<float*>(&lds[0][0]), t.mat, m0 + wm * WM, n0 + wn * WN,
+                                    mirror);
 }
 
 // ---- fp32 kernel ------------------------------------------------------------------------------
@@ -327,7 +392,10 @@ template <bool TP, bool TQ>
 __global__ __launch_bounds__(kThreads) void ns_gemm_f32_kernel(const GemmArgs a) {
   constexpr int BM = 128, BN = 128, BK = 16;
   constexpr int LDR = 128 + 4;   // padded row count per k
-  __shared__ float lds[2][2][BK * LDR];
+  constexpr int kStageFloats = 4 * 32 * (64 + 4);          // epilogue staging, 4 wavefronts
+  constexpr int kTileFloats = 2 * 2 * BK * LDR;
+  __shared__ __attribute__((aligned(16))) float lds_raw[kTileFloats > kStageFloats ? kTileFloats : kStageFloats];
+  float (*lds)[2][BK * LDR] = reinterpret_cast<float (*)[2][BK * LDR]>(lds_raw);
 
   const TileId t = decode_tile(a);
   if (!t.valid) return;
@@ -413,27 +481,8 @@ __global__ __launch_bounds__(kThreads) void ns_gemm_f32_kernel(const GemmArgs a)
     __syncthreads();
   }
 
-  const int mi = a.members ? a.members[t.mat] : t.mat;
-  float post = 1.0f;
-  if (a.post == POST_INV) post = a.scales[mi].inv;
-  else if (a.post == POST_INV2) post = a.scales[mi].inv2;
-  const float* E = a.E ? static_cast<const float*>(a.E) + (size_t)t.mat * a.strideE : nullptr;
-  float* C = static_cast<float*>(a.C) + (size_t)t.mat * a.strideC;
-  const MatStatic* ms = nullptr;
-  void* wptr = nullptr;
-  bool skip_w = false;
-  if (a.epilogue == EPI_UPDATE) {
-    ms = a.stat + mi;
-    wptr = a.dyn[mi].w;
-    skip_w = (a.scales[mi].status & 2u) != 0;
-  }
   const bool mirror = a.symmetric && (t.ti != t.tj);
-  static_for<2>([&](auto i) {
-    static_for<2>([&](auto j) {
-      epilogue_block<float>(a, acc[i][j], t.mat, m0 + wm * 64 + i * 32, n0 + wn * 64 + j * 32, mirror, post, E, C,
-                            ms, wptr, skip_w);
-    });
-  });
+  tile_epilogue<float, 64, 2, 2>(a, acc, lds_raw, t.mat, m0 + wm * 64, n0 + wn * 64, mirror);
 }
 
 template <int BM, int BN>
