@@ -20,6 +20,8 @@
 // fp32 path: v_mfma_f32_32x32x2_f32, 128 x 128 tiles, K step 16.
 #include "mona_internal.h"
 
+#include <cstdlib>
+
 namespace mona {
 
 namespace {
@@ -210,6 +212,16 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs& a, f32x16 (&acc)[M
   const bool w_vec_ok = (wn_real % CH) == 0;
 
   static_for<MI>([&](auto i) {
+    // the band's E operands are fetched up front: their latency overlaps the staging below
+    vec_t ev[PASSES];
+    if (E != nullptr) {
+#pragma unroll
+      for (int pss = 0; pss < PASSES; ++pss) {
+        const int idx = pss * 64 + lane;
+        ev[pss] = *reinterpret_cast<const vec_t*>(E + (size_t)(row_w0 + i * 32 + idx / CPR) * a.lde + col_w0 +
+                                                  (idx % CPR) * CH);
+      }
+    }
     __syncthreads();     // previous band fully consumed (first band: operand tiles no longer read)
     static_for<NI>([&](auto j) {
 #pragma unroll
@@ -234,9 +246,8 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs& a, f32x16 (&acc)[M
         }
       }
       if (E != nullptr) {
-        const vec_t ev = *reinterpret_cast<const vec_t*>(E + (size_t)grow * a.lde + gcol);
 #pragma unroll
-        for (int e = 0; e < CH; ++e) val[e] = post * (a.alpha * val[e] + a.beta * to_f32(ev[e]));
+        for (int e = 0; e < CH; ++e) val[e] = post * (a.alpha * val[e] + a.beta * to_f32(ev[pss][e]));
       } else {
 #pragma unroll
         for (int e = 0; e < CH; ++e) val[e] = post * (a.alpha * val[e]);
@@ -339,49 +350,245 @@ __global__ __launch_bounds__(kThreads) void ns_gemm_bf16_kernel(const GemmArgs a
   Loader<BN, TQ> lq;
   const int KT = a.K / BK;
 
+  // Software pipeline: tile kt+1 travels global -> registers while tile kt is multiplied, and is
+  // written to the other LDS buffer during the last quarter of the step; MFMA fragments are
+  // double-buffered so the reads of quarter kk+1 are in flight while quarter kk is multiplied.
+  const int frow = lane & 31, fchunk = lane >> 5;
+  bf16x8 fa[2][MI], fb[2][NI];
+  auto load_frags = [&](auto slot, int buf, int kk) {
+    const u32x4* __restrict__ ps = lds[buf];
+    const u32x4* __restrict__ qs = lds[buf] + BM * 8;
+    static_for<MI>([&](auto i) {
+      fa[slot][i] = __builtin_bit_cast(bf16x8, ps[lds_slot(wm * WM + i * 32 + frow, kk * 2 + fchunk)]);
+    });
+    static_for<NI>([&](auto j) {
+      fb[slot][j] = __builtin_bit_cast(bf16x8, qs[lds_slot(wn * WN + j * 32 + frow, kk * 2 + fchunk)]);
+    });
+  };
+  auto multiply = [&](auto slot) {
+    static_for<MI>([&](auto i) {
+      static_for<NI>([&](auto j) {
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], acc[i][j], 0, 0, 0);
+      });
+    });
+  };
+  auto kstep = [&](auto has_next, int kt) {
+    const int buf = kt & 1;
+    if constexpr (has_next) {
+      lp.load(P, a.ldp, m0, (kt + 1) * BK);
+      lq.load(Q, a.ldq, n0, (kt + 1) * BK);
+    }
+    // keep the phases of the step in program order: the loads above must be issued a full step
+    // before their data is needed, not sunk next to the LDS writes that consume them
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<BK / 16>([&](auto kk) {
+      if constexpr (kk + 1 < BK / 16) load_frags(IC<(kk + 1) & 1>{}, buf, kk + 1);
+      if constexpr (has_next && kk == BK / 16 - 1) {
+        lp.store(lds[buf ^ 1]);
+        lq.store(lds[buf ^ 1] + BM * 8);
+      }
+      multiply(IC<kk & 1>{});
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    __syncthreads();
+    if constexpr (has_next) load_frags(IC<0>{}, buf ^ 1, 0);
+  };
+
   lp.load(P, a.ldp, m0, 0);
   lq.load(Q, a.ldq, n0, 0);
   lp.store(lds[0]);
   lq.store(lds[0] + BM * 8);
   __syncthreads();
-
-  const int frow = lane & 31, fchunk = lane >> 5;
-  for (int kt = 0; kt < KT; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < KT) {
-      lp.load(P, a.ldp, m0, (kt + 1) * BK);
-      lq.load(Q, a.ldq, n0, (kt + 1) * BK);
-    }
-    const u32x4* __restrict__ lp_s = lds[buf];
-    const u32x4* __restrict__ lq_s = lds[buf] + BM * 8;
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 fa[MI], fb[NI];
-#pragma unroll
-      for (int i = 0; i < MI; ++i) {
-        const u32x4 u = lp_s[lds_slot(wm * WM + i * 32 + frow, kk * 2 + fchunk)];
-        fa[i] = __builtin_bit_cast(bf16x8, u);
-      }
-#pragma unroll
-      for (int j = 0; j < NI; ++j) {
-        const u32x4 u = lq_s[lds_slot(wn * WN + j * 32 + frow, kk * 2 + fchunk)];
-        fb[j] = __builtin_bit_cast(bf16x8, u);
-      }
-#pragma unroll
-      for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NI; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < KT) {
-      lp.store(lds[buf ^ 1]);
-      lq.store(lds[buf ^ 1] + BM * 8);
-    }
-    __syncthreads();
-  }
+  load_frags(IC<0>{}, 0, 0);
+  for (int kt = 0; kt + 1 < KT; ++kt) kstep(IC<1>{}, kt);
+  kstep(IC<0>{}, KT - 1);
 
   const bool mirror = a.symmetric && (t.ti != t.tj);
   tile_epilogue<bf16_t, WN, MI, NI>(a, acc, reinterpret_cast<float*>(&lds[0][0]), t.mat, m0 + wm * WM, n0 + wn * WN,
+                                    mirror);
+}
+
+// ---- bf16 kernel, direct-to-LDS pipeline ------------------------------------------------------
+// 256 x 256 tile, 512 threads = 8 wavefronts (2 x 4, each 128 x 64), two per SIMD so that one
+// multiplies while the other waits on LDS.  Operand tiles go from global memory straight into
+// LDS (global_load_lds, 16 bytes per lane, no staging registers) through a ring of 4 stages of
+// K = 32, so a tile is requested three steps (~3000 MFMA cycles per SIMD) before it is used.
+//
+// LDS layouts of one 256 x 32 operand tile (16 KB), in 16-byte chunks:
+//   row-major operand (K contiguous in memory): 256 rows x 4 chunks, chunk c of row r at
+//     r * 4 + (c ^ ((r >> 2) & 3)); a fragment is one ds_read_b128 per lane (8 consecutive k);
+//   K-major operand (stored K x M): 32 k-rows x 32 chunks, chunk c of k-row k at
+//     k * 32 + (c ^ ((k & 3) << 2)); a fragment is two ds_read_b64_tr_b16 per lane: 16 lanes
+//     fetch a 4 (k) x 16 (m) block and each receives the 4 k-values of one m.
+// A direct load writes lane l's 16 bytes at (wave-uniform base) + 16 l, so the swizzle is applied
+// by choosing which global chunk each lane fetches.
+constexpr int kThreadsV2 = 512;
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+#define MONA_AS1 __attribute__((address_space(1)))
+#define MONA_AS3 __attribute__((address_space(3)))
+
+template <bool TP, bool TQ>
+__global__ __launch_bounds__(kThreadsV2) void ns_gemm_bf16_v2_kernel(const GemmArgs a) {
+  constexpr int BM = 256, BN = 256, BK = 32, STAGES = 4;
+  constexpr int WM = 128, WN = 64, MI = 4, NI = 2;
+  constexpr int TILE_U = 1024;                 // 16-byte units per operand tile
+  constexpr int STAGE_U = 2 * TILE_U;          // P tile then Q tile
+  __shared__ __attribute__((aligned(16))) u32x4 lds[STAGES * STAGE_U];   // 128 KB
+
+  const TileId t = decode_tile(a);
+  if (!t.valid) return;
+  const bf16_t* __restrict__ P = static_cast<const bf16_t*>(a.P) + (size_t)t.mat * a.strideP;
+  const bf16_t* __restrict__ Q = static_cast<const bf16_t*>(a.Q) + (size_t)t.mat * a.strideQ;
+  const int m0 = t.ti * BM, n0 = t.tj * BN;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 2, wn = wave & 3;
+
+  // ---- direct loads: 2 instructions per wavefront per operand per stage ----
+  const bf16_t* gp[2];
+  const bf16_t* gq[2];
+  static_for<2>([&](auto q) {
+    const int S = (wave * 2 + q) * 64 + lane;
+    if constexpr (!TP) {
+      const int row = S >> 2, c = (S & 3) ^ ((row >> 2) & 3);
+      gp[q] = P + (size_t)(m0 + row) * a.ldp + c * 8;
+    } else {
+      const int k = S >> 5, c = (S & 31) ^ ((k & 3) << 2);
+      gp[q] = P + (size_t)k * a.ldp + m0 + c * 8;
+    }
+    if constexpr (!TQ) {
+      const int row = S >> 2, c = (S & 3) ^ ((row >> 2) & 3);
+      gq[q] = Q + (size_t)(n0 + row) * a.ldq + c * 8;
+    } else {
+      const int k = S >> 5, c = (S & 31) ^ ((k & 3) << 2);
+      gq[q] = Q + (size_t)k * a.ldq + n0 + c * 8;
+    }
+  });
+  const size_t incp = TP ? (size_t)BK * a.ldp : (size_t)BK;   // elements per K step
+  const size_t incq = TQ ? (size_t)BK * a.ldq : (size_t)BK;
+  auto issue = [&](auto stage, int kt) {
+    static_for<2>([&](auto q) {
+      u32x4* dp = lds + stage * STAGE_U + (wave * 2 + q) * 64;
+      u32x4* dq = dp + TILE_U;
+      __builtin_amdgcn_global_load_lds((const MONA_AS1 void*)(gp[q] + kt * incp), (MONA_AS3 void*)dp, 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const MONA_AS1 void*)(gq[q] + kt * incq), (MONA_AS3 void*)dq, 16, 0, 0);
+    });
+  };
+
+  // ---- fragment addresses (bytes inside an operand tile), per lane ----
+  // row-major layout: two variants of the chunk term, one per 16-wide k step
+  const int rsw = ((lane & 31) >> 2) & 3;                 // (row >> 2) & 3, the same for every block
+  const int r_off[2] = {((lane & 31) * 4 + (((0 + (lane >> 5)) ^ rsw))) * 16,
+                        ((lane & 31) * 4 + (((2 + (lane >> 5)) ^ rsw))) * 16};
+  // K-major layout: k-row and 16-byte chunk this lane fetches for a 4 x 16 transposed block
+  const int t_k = 8 * (lane >> 5) + ((lane & 15) >> 2);    // + 16 kk + 4 quad
+  const int t_x = (lane & 15) >> 2;                        // k & 3 of that row: the swizzle term
+  const int t_nl = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);  // m inside the 32-wide block
+  int ta_off[MI], tb_off[NI];
+  static_for<MI>([&](auto i) {
+    const int c = (wm * (WM / 8) + i * 4 + (t_nl >> 3)) ^ (t_x << 2);
+    ta_off[i] = t_k * 512 + c * 16 + (t_nl & 7) * 2;
+  });
+  static_for<NI>([&](auto j) {
+    const int c = (wn * (WN / 8) + j * 4 + (t_nl >> 3)) ^ (t_x << 2);
+    tb_off[j] = t_k * 512 + c * 16 + (t_nl & 7) * 2;
+  });
+
+  f32x16 acc[MI][NI];
+  static_for<MI>([&](auto i) {
+    static_for<NI>([&](auto j) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+    });
+  });
+
+  auto frag_r = [&](const char* tile, int blk_row, auto kk) -> bf16x8 {
+    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(tile + blk_row * 64 + r_off[kk]));
+  };
+  // Transposed fragments are read with inline assembly: the compiler cannot tell that these LDS
+  // reads do not touch the stages still being filled by direct loads and would wait for all of
+  // those first.  The reads return through the LGKM counter; wait_frags() below waits for it.
+  auto frag_t = [&](uint32_t tile_addr, int off, auto kk, u32x2& lo, u32x2& hi) {
+    const uint32_t p0 = tile_addr + off + kk * (16 * 512);
+    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(p0));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:2048" : "=v"(hi) : "v"(p0));
+  };
+  auto compute = [&](auto stage) {
+    const char* tp = reinterpret_cast<const char*>(lds + stage * STAGE_U);
+    const char* tq = tp + TILE_U * 16;
+    const uint32_t tp_addr = (uint32_t)(uintptr_t)(MONA_AS3 const char*)tp;
+    const uint32_t tq_addr = tp_addr + TILE_U * 16;
+    static_for<BK / 16>([&](auto kk) {
+      bf16x8 fa[MI], fb[NI];
+      u32x2 ta[MI][2], tb[NI][2];
+      static_for<MI>([&](auto i) {
+        if constexpr (!TP) fa[i] = frag_r(tp, wm * WM + i * 32, kk);
+        else frag_t(tp_addr, ta_off[i], kk, ta[i][0], ta[i][1]);
+      });
+      static_for<NI>([&](auto j) {
+        if constexpr (!TQ) fb[j] = frag_r(tq, wn * WN + j * 32, kk);
+        else frag_t(tq_addr, tb_off[j], kk, tb[j][0], tb[j][1]);
+      });
+      if constexpr (TP) {
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(ta[0][0]), "+v"(ta[0][1]), "+v"(ta[1][0]), "+v"(ta[1][1]), "+v"(ta[2][0]), "+v"(ta[2][1]),
+                       "+v"(ta[3][0]), "+v"(ta[3][1]));
+        static_for<MI>([&](auto i) {
+          const u32x4 v = {ta[i][0].x, ta[i][0].y, ta[i][1].x, ta[i][1].y};
+          fa[i] = __builtin_bit_cast(bf16x8, v);
+        });
+      }
+      if constexpr (TQ) {
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(tb[0][0]), "+v"(tb[0][1]), "+v"(tb[1][0]), "+v"(tb[1][1]));
+        static_for<NI>([&](auto j) {
+          const u32x4 v = {tb[j][0].x, tb[j][0].y, tb[j][1].x, tb[j][1].y};
+          fb[j] = __builtin_bit_cast(bf16x8, v);
+        });
+      }
+      static_for<MI>([&](auto i) {
+        static_for<NI>([&](auto j) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        });
+      });
+    });
+  };
+
+  // s_waitcnt vmcnt(n), leaving the other counters alone (gfx9 encoding)
+#define MONA_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
+
+  const int KT = a.K / BK;      // a multiple of 4: K is a multiple of 128
+  issue(IC<0>{}, 0);
+  issue(IC<1>{}, 1);
+  issue(IC<2>{}, 2);
+  // each wavefront has 4 loads per stage in flight; stage kt is complete once at most 8 newer remain.
+  // A bare s_barrier (no fence) is used inside the pipeline: a fence would drain every load in flight.
+  int kt = 0;
+  for (; kt + 4 < KT; kt += 4) {
+    static_for<4>([&](auto u) {
+      MONA_WAIT_VM(8);
+      __builtin_amdgcn_s_barrier();        // stage kt landed for everyone, stage kt+3 free for everyone
+      issue(IC<(u + 3) & 3>{}, kt + u + 3);
+      compute(u);
+    });
+  }
+  // last four steps: one more tile to request, then drain
+  MONA_WAIT_VM(8);
+  __builtin_amdgcn_s_barrier();
+  issue(IC<3>{}, kt + 3);
+  compute(IC<0>{});
+  MONA_WAIT_VM(8);
+  __builtin_amdgcn_s_barrier();
+  compute(IC<1>{});
+  MONA_WAIT_VM(4);
+  __builtin_amdgcn_s_barrier();
+  compute(IC<2>{});
+  MONA_WAIT_VM(0);
+  __builtin_amdgcn_s_barrier();
+  compute(IC<3>{});
+#undef MONA_WAIT_VM
+
+  const bool mirror = a.symmetric && (t.ti != t.tj);
+  tile_epilogue<bf16_t, WN, MI, NI>(a, acc, reinterpret_cast<float*>(&lds[0]), t.mat, m0 + wm * WM, n0 + wn * WN,
                                     mirror);
 }
 
@@ -496,6 +703,9 @@ hipError_t launch_bf16(const GemmArgs& a, bool tp, bool tq, int grid, hipStream_
 
 }  // namespace
 
+// development switch: MONA_GEMM_V1=1 selects the register-staged 256-tile kernel
+static const bool g_use_v2 = []() { const char* e = getenv("MONA_GEMM_V1"); return !(e && e[0] == '1'); }();
+
 hipError_t launch_ns_gemm(const GemmArgs& a, int tile, bool transP, bool transQ, bool f32, hipStream_t s) {
   const long long total = (long long)a.tiles_per_mat * a.count;
   if (total <= 0) return hipSuccess;
@@ -506,6 +716,13 @@ hipError_t launch_ns_gemm(const GemmArgs& a, int tile, bool transP, bool transQ,
     if (!transP && !transQ) hipLaunchKernelGGL((ns_gemm_f32_kernel<false, false>), dim3(grid), dim3(kThreads), 0, s, a);
     else if (!transP && transQ) hipLaunchKernelGGL((ns_gemm_f32_kernel<false, true>), dim3(grid), dim3(kThreads), 0, s, a);
     else if (transP && transQ) hipLaunchKernelGGL((ns_gemm_f32_kernel<true, true>), dim3(grid), dim3(kThreads), 0, s, a);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+  }
+  if (tile == 256 && g_use_v2) {
+    if (!transP && !transQ) hipLaunchKernelGGL((ns_gemm_bf16_v2_kernel<false, false>), dim3(grid), dim3(kThreadsV2), 0, s, a);
+    else if (!transP && transQ) hipLaunchKernelGGL((ns_gemm_bf16_v2_kernel<false, true>), dim3(grid), dim3(kThreadsV2), 0, s, a);
+    else if (transP && transQ) hipLaunchKernelGGL((ns_gemm_bf16_v2_kernel<true, true>), dim3(grid), dim3(kThreadsV2), 0, s, a);
     else return hipErrorInvalidValue;
     return hipGetLastError();
   }
