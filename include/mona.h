@@ -172,7 +172,8 @@ int mona_last_step_times(mona_state* st, float* ms_out);
  * by its own pair of events.  mona_last_step_launches waits for the step and fills up to
  * max_records entries (out may be NULL to query the count).
  *   kind: 0 = Gram (X X^T), 1 = poly (b S + c S S), 2 = apply (a X + B X)
- *   flops: MFMA flop the launch issues (tiles x 2 x tile^2 x K), padding included      */
+ *   tile:  block tile of the kernel, rows * 1000 + columns (e.g. 256128)
+ *   flops: MFMA flop the launch issues (tiles x 2 x rows x columns x K), padding included */
 typedef struct mona_launch_time {
   int32_t kind, group, iter, tile;
   int32_t m, n, count;   /* shape of the group's matrices and how many there are */

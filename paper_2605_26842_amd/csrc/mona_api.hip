@@ -8,6 +8,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <new>
@@ -231,9 +232,11 @@ struct mona_state {
 
 namespace {
 
-// tile used by one product of a group
-int pick_tile(const Group& g, int kind, int count) {
-  if (g.f32 || g.gran < 256) return 128;
+struct TileShape { int bm, bn; };
+
+// block tile used by one product of a group
+TileShape pick_tile(const Group& g, int kind, int count) {
+  if (g.f32 || g.gran < 256) return {128, 128};
   long long tiles;
   if (kind == OP_APPLY) {
     tiles = (long long)(g.rows_pad / 256) * (g.cols_pad / 256) * count;
@@ -241,15 +244,16 @@ int pick_tile(const Group& g, int kind, int count) {
     const long long t = g.p_pad / 256;
     tiles = t * (t + 1) / 2 * count;
   }
-  return tiles >= 192 ? 256 : 128;
+  if (tiles < 192) return {128, 128};       // too few large tiles to fill 256 CUs
+  return {256, 256};
 }
 
-double gemm_flops(const GemmArgs& a, int tile) {
-  return 2.0 * tile * tile * (double)a.K * a.tiles_per_mat * a.count;
+double gemm_flops(const GemmArgs& a) {
+  return 2.0 * a.tile_m * a.tile_n * (double)a.K * a.tiles_per_mat * a.count;
 }
 
-void fill_gemm(const mona_state* st, const Group& g, int kind, int tile, int src, const mona_hparams& hp, bool first,
-               bool last, GemmArgs& a, bool& tp, bool& tq) {
+void fill_gemm(const mona_state* st, const Group& g, int kind, TileShape tile, int src, const mona_hparams& hp,
+               bool first, bool last, GemmArgs& a, bool& tp, bool& tq) {
   const Layout& L = st->L;
   memset(&a, 0, sizeof a);
   const int cnt = (int)g.members.size();
@@ -308,9 +312,18 @@ void fill_gemm(const mona_state* st, const Group& g, int kind, int tile, int src
       a.o_scale = hp.lr * hp.gamma_coeff * sqrtf((float)std::max(g.m, g.n));
     }
   }
-  a.tiles_m = a.M / tile;
-  a.tiles_n = a.N / tile;
-  a.tiles_per_mat = a.symmetric ? a.tiles_n * (a.tiles_n + 1) / 2 : a.tiles_m * a.tiles_n;
+  a.tile_m = tile.bm;
+  a.tile_n = tile.bn;
+  a.sym_ratio = tile.bm / tile.bn;
+  a.tiles_m = a.M / tile.bm;
+  a.tiles_n = a.N / tile.bn;
+  if (a.symmetric) {
+    // row block ti keeps the column blocks from its diagonal on
+    a.tiles_per_mat = 0;
+    for (int ti = 0; ti < a.tiles_m; ++ti) a.tiles_per_mat += a.tiles_n - a.sym_ratio * ti;
+  } else {
+    a.tiles_per_mat = a.tiles_m * a.tiles_n;
+  }
 }
 
 int check_hparams(const mona_hparams* hp) {
@@ -527,7 +540,7 @@ int mona_step(mona_state* st, const mona_matrix* mats, int32_t count, const mona
       for (int kind = OP_GRAM; kind <= OP_APPLY; ++kind) {
         GemmArgs a;
         bool tp = false, tq = false;
-        const int tile = pick_tile(g, kind, cnt);
+        const TileShape tile = pick_tile(g, kind, cnt);
         fill_gemm(st, g, kind, tile, src, *hp, t == 0, t == T - 1, a, tp, tq);
         LaunchRecord rec;
         const bool each = st->profiling > 1;
@@ -535,11 +548,11 @@ int mona_step(mona_state* st, const mona_matrix* mats, int32_t count, const mona
           if (!get_event_pair(st, &rec.e0, &rec.e1)) return fail(MONA_EHIP, "hipEventCreate failed");
           HIP_TRY(hipEventRecord(rec.e0, s));
         }
-        HIP_TRY(launch_ns_gemm(a, tile, tp, tq, g.f32, s));
+        HIP_TRY(launch_ns_gemm(a, tile.bm, tp, tq, g.f32, s));
         if (each) {
           HIP_TRY(hipEventRecord(rec.e1, s));
-          rec.kind = kind; rec.group = (int)gi; rec.iter = t; rec.tile = tile;
-          rec.flops = gemm_flops(a, tile);
+          rec.kind = kind; rec.group = (int)gi; rec.iter = t; rec.tile = tile.bm * 1000 + tile.bn;
+          rec.flops = gemm_flops(a);
           st->records.push_back(rec);
         }
       }
@@ -693,9 +706,9 @@ int mona_plan_info(mona_state* st, int32_t ns_steps, int64_t* launches_out, doub
     for (int kind = OP_GRAM; kind <= OP_APPLY; ++kind) {
       GemmArgs a;
       bool tp, tq;
-      const int tile = pick_tile(g, kind, cnt);
+      const TileShape tile = pick_tile(g, kind, cnt);
       fill_gemm(st, g, kind, tile, 0, hp, false, false, a, tp, tq);
-      flops += gemm_flops(a, tile) * ns_steps;
+      flops += gemm_flops(a) * ns_steps;
       launches += ns_steps;
     }
   }

@@ -60,6 +60,8 @@ struct GemmArgs {
   int64_t strideP, strideQ, strideE, strideC;  // elements between consecutive matrices of the group
   int32_t ldp, ldq, lde, ldc;
   int32_t M, N, K;          // padded problem size, multiples of the tile
+  int32_t tile_m, tile_n;   // BM, BN of the kernel that will run
+  int32_t sym_ratio;        // BM / BN (symmetric products walk the block triangle with it)
   int32_t tiles_m, tiles_n; // M / BM, N / BN
   int32_t tiles_per_mat;    // tiles_m * tiles_n, or the triangle count when symmetric
   int32_t count;            // matrices in the group

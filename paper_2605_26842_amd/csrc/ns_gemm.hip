@@ -20,7 +20,9 @@
 // fp32 path: v_mfma_f32_32x32x2_f32, 128 x 128 tiles, K step 16.
 #include "mona_internal.h"
 
+#include <cstdio>
 #include <cstdlib>
+#include <type_traits>
 
 namespace mona {
 
@@ -63,10 +65,12 @@ __device__ __forceinline__ TileId decode_tile(const GemmArgs& a) {
   t.mat = logical / a.tiles_per_mat;
   int r = logical - t.mat * a.tiles_per_mat;
   if (a.symmetric) {
+    // row block ti holds the column blocks from its diagonal onwards: tj >= ratio * ti,
+    // ratio = tile rows / tile columns
     int ti = 0, row = a.tiles_n;
-    while (r >= row) { r -= row; --row; ++ti; }
+    while (r >= row) { r -= row; row -= a.sym_ratio; ++ti; }
     t.ti = ti;
-    t.tj = ti + r;
+    t.tj = ti * a.sym_ratio + r;
   } else {
     t.ti = r / a.tiles_n;
     t.tj = r - t.ti * a.tiles_n;
@@ -177,148 +181,191 @@ __device__ __forceinline__ float to_f32(float v) { return v; }
 // 32-row band at a time, so that every global access of the epilogue is a 16-byte vector that
 // runs along a row:  out = post * (beta * E + alpha * acc), then either a plain store (plus the
 // mirrored store of a symmetric product) or the parameter update of Eq. muon_update.
+// Orders the LDS traffic of one wavefront for the compiler (lanes exchange data through a region
+// only this wavefront touches; the LDS unit itself executes a wavefront's accesses in order).
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 template <typename T> struct Chunk;           // 16 bytes of T
 template <> struct Chunk<bf16_t> { static constexpr int N = 8; typedef bf16x8 vec; };
 template <> struct Chunk<float> { static constexpr int N = 4; typedef f32x4 vec; };
 
 template <typename T, int WN, int MI, int NI>
-__device__ __forceinline__ void tile_epilogue(const GemmArgs& a, f32x16 (&acc)[MI][NI], float* __restrict__ lds_f,
-                                              int tmat, int row_w0, int col_w0, bool mirror) {
-  constexpr int CH = Chunk<T>::N;
+struct Epilogue {
+  static constexpr int CH = Chunk<T>::N;
   typedef typename Chunk<T>::vec vec_t;
-  constexpr int LDW = WN + 4;                    // floats per staged row (+4: the two half-waves
+  static constexpr int LDW = WN + 4;             // floats per staged row (+4: the two half-waves
                                                  // write rows 4 apart, keep them on different banks)
-  constexpr int CPR = WN / CH;                   // chunks per row
-  constexpr int PASSES = 32 * CPR / 64;          // chunks per lane per band
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  float* __restrict__ stage = lds_f + wave * (32 * LDW);
+  static constexpr int CPR = WN / CH;            // chunks per row
+  static constexpr int PASSES = 32 * CPR / 64;   // chunks per lane per band
 
-  const int mi = a.members ? a.members[tmat] : tmat;
-  float post = 1.0f;
-  if (a.post == POST_INV) post = a.scales[mi].inv;
-  else if (a.post == POST_INV2) post = a.scales[mi].inv2;
-  const T* __restrict__ E = a.E ? static_cast<const T*>(a.E) + (size_t)tmat * a.strideE : nullptr;
-  T* __restrict__ C = static_cast<T*>(a.C) + (size_t)tmat * a.strideC;
-  const bool update = a.epilogue == EPI_UPDATE;
-  int wm_real = 0, wn_real = 0, w_is_bf16 = 0;
-  bool skip_w = true;
-  void* wptr = nullptr;
-  if (update) {
-    const MatStatic& ms = a.stat[mi];
-    wm_real = ms.m; wn_real = ms.n; w_is_bf16 = ms.w_dtype;
-    wptr = a.dyn[mi].w;
-    skip_w = (a.scales[mi].status & 2u) != 0;
-  }
-  const bool w_vec_ok = (wn_real % CH) == 0;
+  const GemmArgs& a;
+  int lane, row_w0, col_w0;
+  bool mirror, update, skip_w, w_vec_ok, w_pref;
+  float post;
+  const T* __restrict__ E;
+  T* __restrict__ C;
+  int wm_real, wn_real, w_is_bf16;
+  void* wptr;
+  vec_t ev[2][PASSES];       // E operands of the current and the next band
+  bf16x8 wv[2][PASSES];      // bf16 parameters of the current and the next band (update only)
 
-  static_for<MI>([&](auto i) {
-    // the band's E operands are fetched up front: their latency overlaps the staging below
-    vec_t ev[PASSES];
-    if (E != nullptr) {
-#pragma unroll
-      for (int pss = 0; pss < PASSES; ++pss) {
-        const int idx = pss * 64 + lane;
-        ev[pss] = *reinterpret_cast<const vec_t*>(E + (size_t)(row_w0 + i * 32 + idx / CPR) * a.lde + col_w0 +
-                                                  (idx % CPR) * CH);
-      }
+  __device__ __forceinline__ Epilogue(const GemmArgs& args, int tmat, int row0, int col0, bool mir)
+      : a(args), lane(threadIdx.x & 63), row_w0(row0), col_w0(col0), mirror(mir) {
+    const int mi = a.members ? a.members[tmat] : tmat;
+    post = 1.0f;
+    if (a.post == POST_INV) post = a.scales[mi].inv;
+    else if (a.post == POST_INV2) post = a.scales[mi].inv2;
+    E = a.E ? static_cast<const T*>(a.E) + (size_t)tmat * a.strideE : nullptr;
+    C = static_cast<T*>(a.C) + (size_t)tmat * a.strideC;
+    update = a.epilogue == EPI_UPDATE;
+    wm_real = wn_real = w_is_bf16 = 0;
+    skip_w = true;
+    wptr = nullptr;
+    if (update) {
+      const MatStatic& ms = a.stat[mi];
+      wm_real = ms.m; wn_real = ms.n; w_is_bf16 = ms.w_dtype;
+      wptr = a.dyn[mi].w;
+      skip_w = (a.scales[mi].status & 2u) != 0;
     }
-    __syncthreads();     // previous band fully consumed (first band: operand tiles no longer read)
-    static_for<NI>([&](auto j) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int r = (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-        stage[r * LDW + j * 32 + (lane & 31)] = acc[i][j][v];
-      }
-    });
-    __syncthreads();
+    w_vec_ok = (wn_real % CH) == 0;
+    // bf16 parameters whose rows are whole 16-byte chunks are fetched a band ahead
+    w_pref = update && !skip_w && w_is_bf16 && CH == 8 && w_vec_ok;
+  }
+
+  // Issue the global loads band `band` needs (E chunks, and the parameter chunks of an update)
+  // into slot band & 1.  Called a band ahead so the latency overlaps other work.
+  template <int BAND>
+  __device__ __forceinline__ void prefetch() {
+    constexpr int slot = BAND & 1;
 #pragma unroll
     for (int pss = 0; pss < PASSES; ++pss) {
       const int idx = pss * 64 + lane;
-      const int r = idx / CPR, ch = idx % CPR;
-      const int grow = row_w0 + i * 32 + r, gcol = col_w0 + ch * CH;
-      float val[CH];
-      {
-        const f32x4* src = reinterpret_cast<const f32x4*>(stage + r * LDW + ch * CH);
+      const int grow = row_w0 + BAND * 32 + idx / CPR, gcol = col_w0 + (idx % CPR) * CH;
+      if (E != nullptr) ev[slot][pss] = *reinterpret_cast<const vec_t*>(E + (size_t)grow * a.lde + gcol);
+      if constexpr (CH == 8) {
+        if (w_pref && grow < wm_real && gcol + CH <= wn_real)
+          wv[slot][pss] = *reinterpret_cast<const bf16x8*>(static_cast<const bf16_t*>(wptr) +
+                                                          (size_t)grow * wn_real + gcol);
+      }
+    }
+  }
+
+  // prefetch<0>() must have been called.  lds_f: LDS scratch of (#wavefronts x 32 x LDW) floats.
+  __device__ __forceinline__ void run(f32x16 (&acc)[MI][NI], float* __restrict__ lds_f) {
+    const int wave = threadIdx.x >> 6;
+    float* __restrict__ stage = lds_f + wave * (32 * LDW);   // private to this wavefront
+    // Every wavefront has finished reading operand tiles before any staging overwrites them.  From
+    // here on a wavefront only touches its own staging rows, so no workgroup barrier (and above all
+    // no fence, which would wait for the global stores in flight) is needed between bands.
+    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wavefront's LDS reads have returned
+    __builtin_amdgcn_s_barrier();
+    static_for<MI>([&](auto i) {
+      constexpr int slot = i & 1;
+      if constexpr (i + 1 < MI) prefetch<i + 1>();
+      wave_sync();         // previous band fully consumed
+      static_for<NI>([&](auto j) {
 #pragma unroll
-        for (int q = 0; q < CH / 4; ++q) {
-          const f32x4 t4 = src[q];
-          val[q * 4 + 0] = t4.x; val[q * 4 + 1] = t4.y; val[q * 4 + 2] = t4.z; val[q * 4 + 3] = t4.w;
+        for (int v = 0; v < 16; ++v) {
+          const int r = (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+          stage[r * LDW + j * 32 + (lane & 31)] = acc[i][j][v];
         }
-      }
-      if (E != nullptr) {
+      });
+      wave_sync();
 #pragma unroll
-        for (int e = 0; e < CH; ++e) val[e] = post * (a.alpha * val[e] + a.beta * to_f32(ev[pss][e]));
-      } else {
+      for (int pss = 0; pss < PASSES; ++pss) {
+        const int idx = pss * 64 + lane;
+        const int r = idx / CPR, ch = idx % CPR;
+        const int grow = row_w0 + i * 32 + r, gcol = col_w0 + ch * CH;
+        float val[CH];
+        {
+          const f32x4* src = reinterpret_cast<const f32x4*>(stage + r * LDW + ch * CH);
 #pragma unroll
-        for (int e = 0; e < CH; ++e) val[e] = post * (a.alpha * val[e]);
-      }
-      vec_t ov;
-#pragma unroll
-      for (int e = 0; e < CH; ++e) ov[e] = (T)val[e];
-      if (!update || a.store_out) *reinterpret_cast<vec_t*>(C + (size_t)grow * a.ldc + gcol) = ov;
-      if (mirror) {
-        // keep the rounded result for the transposed store below
-        f32x4* dst = reinterpret_cast<f32x4*>(stage + r * LDW + ch * CH);
-#pragma unroll
-        for (int q = 0; q < CH / 4; ++q) {
-          f32x4 t4 = {to_f32(ov[q * 4 + 0]), to_f32(ov[q * 4 + 1]), to_f32(ov[q * 4 + 2]), to_f32(ov[q * 4 + 3])};
-          dst[q] = t4;
-        }
-      }
-      if (update && !skip_w && grow < wm_real) {
-        // W <- (1 - eta lambda) W - eta gamma O, O as stored in the working precision
-        const size_t wi = (size_t)grow * wn_real + gcol;
-        if (w_vec_ok && gcol + CH <= wn_real) {
-          if (w_is_bf16) {
-            typedef bf16_t wv_t __attribute__((ext_vector_type(CH)));
-            wv_t* wp = reinterpret_cast<wv_t*>(static_cast<bf16_t*>(wptr) + wi);
-            wv_t wv = *wp;
-#pragma unroll
-            for (int e = 0; e < CH; ++e) wv[e] = (bf16_t)(a.w_keep * (float)wv[e] - a.o_scale * to_f32(ov[e]));
-            *wp = wv;
-          } else {
-            f32x4* wp = reinterpret_cast<f32x4*>(static_cast<float*>(wptr) + wi);
-#pragma unroll
-            for (int q = 0; q < CH / 4; ++q) {
-              f32x4 wv = wp[q];
-#pragma unroll
-              for (int e = 0; e < 4; ++e) wv[e] = a.w_keep * wv[e] - a.o_scale * to_f32(ov[q * 4 + e]);
-              wp[q] = wv;
-            }
+          for (int q = 0; q < CH / 4; ++q) {
+            const f32x4 t4 = src[q];
+            val[q * 4 + 0] = t4.x; val[q * 4 + 1] = t4.y; val[q * 4 + 2] = t4.z; val[q * 4 + 3] = t4.w;
           }
+        }
+        if (E != nullptr) {
+#pragma unroll
+          for (int e = 0; e < CH; ++e) val[e] = post * (a.alpha * val[e] + a.beta * to_f32(ev[slot][pss][e]));
         } else {
 #pragma unroll
-          for (int e = 0; e < CH; ++e) {
-            if (gcol + e < wn_real) {
-              if (w_is_bf16) {
-                bf16_t* w = static_cast<bf16_t*>(wptr) + wi + e;
-                *w = (bf16_t)(a.w_keep * (float)*w - a.o_scale * to_f32(ov[e]));
-              } else {
-                float* w = static_cast<float*>(wptr) + wi + e;
-                *w = a.w_keep * *w - a.o_scale * to_f32(ov[e]);
+          for (int e = 0; e < CH; ++e) val[e] = post * (a.alpha * val[e]);
+        }
+        vec_t ov;
+#pragma unroll
+        for (int e = 0; e < CH; ++e) ov[e] = (T)val[e];
+        if (!update || a.store_out) *reinterpret_cast<vec_t*>(C + (size_t)grow * a.ldc + gcol) = ov;
+        if (mirror) {
+          // keep the rounded result for the transposed store below
+          f32x4* dst = reinterpret_cast<f32x4*>(stage + r * LDW + ch * CH);
+#pragma unroll
+          for (int q = 0; q < CH / 4; ++q) {
+            f32x4 t4 = {to_f32(ov[q * 4 + 0]), to_f32(ov[q * 4 + 1]), to_f32(ov[q * 4 + 2]), to_f32(ov[q * 4 + 3])};
+            dst[q] = t4;
+          }
+        }
+        if (update && !skip_w && grow < wm_real) {
+          // W <- (1 - eta lambda) W - eta gamma O, O as stored in the working precision
+          const size_t wi = (size_t)grow * wn_real + gcol;
+          if (w_vec_ok && gcol + CH <= wn_real) {
+            if (w_is_bf16) {
+              typedef bf16_t wv_t __attribute__((ext_vector_type(CH)));
+              wv_t* wp = reinterpret_cast<wv_t*>(static_cast<bf16_t*>(wptr) + wi);
+              wv_t w_in;
+              if constexpr (CH == 8) w_in = wv[slot][pss];
+              else w_in = *wp;
+#pragma unroll
+              for (int e = 0; e < CH; ++e) w_in[e] = (bf16_t)(a.w_keep * (float)w_in[e] - a.o_scale * to_f32(ov[e]));
+              *wp = w_in;
+            } else {
+              f32x4* wp = reinterpret_cast<f32x4*>(static_cast<float*>(wptr) + wi);
+#pragma unroll
+              for (int q = 0; q < CH / 4; ++q) {
+                f32x4 w4 = wp[q];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w4[e] = a.w_keep * w4[e] - a.o_scale * to_f32(ov[q * 4 + e]);
+                wp[q] = w4;
+              }
+            }
+          } else {
+#pragma unroll
+            for (int e = 0; e < CH; ++e) {
+              if (gcol + e < wn_real) {
+                if (w_is_bf16) {
+                  bf16_t* w = static_cast<bf16_t*>(wptr) + wi + e;
+                  *w = (bf16_t)(a.w_keep * (float)*w - a.o_scale * to_f32(ov[e]));
+                } else {
+                  float* w = static_cast<float*>(wptr) + wi + e;
+                  *w = a.w_keep * *w - a.o_scale * to_f32(ov[e]);
+                }
               }
             }
           }
         }
       }
-    }
-    if (mirror) {
-      // transposed copy of this band: C[col][row], 16-byte pieces along the band's 32 rows
-      __syncthreads();
-      constexpr int RCH = 32 / CH;               // row-chunks per band
-      constexpr int MPASSES = WN * RCH / 64;
+      if (mirror) {
+        // transposed copy of this band: C[col][row], 16-byte pieces along the band's 32 rows
+        wave_sync();
+        constexpr int RCH = 32 / CH;               // row-chunks per band
+        constexpr int MPASSES = WN * RCH / 64;
 #pragma unroll
-      for (int pss = 0; pss < MPASSES; ++pss) {
-        const int idx = pss * 64 + lane;
-        const int c = idx % WN, rc = idx / WN;
-        vec_t ov;
+        for (int pss = 0; pss < MPASSES; ++pss) {
+          const int idx = pss * 64 + lane;
+          const int c = idx % WN, rc = idx / WN;
+          vec_t ov;
 #pragma unroll
-        for (int e = 0; e < CH; ++e) ov[e] = (T)stage[(rc * CH + e) * LDW + c];
-        *reinterpret_cast<vec_t*>(C + (size_t)(col_w0 + c) * a.ldc + row_w0 + i * 32 + rc * CH) = ov;
+          for (int e = 0; e < CH; ++e) ov[e] = (T)stage[(rc * CH + e) * LDW + c];
+          *reinterpret_cast<vec_t*>(C + (size_t)(col_w0 + c) * a.ldc + row_w0 + i * 32 + rc * CH) = ov;
+        }
       }
-    }
-  });
-}
+    });
+  }
+};
 
 // ---- bf16 kernel -----------------------------------------------------------------------------
 template <int BM, int BN, bool TP, bool TQ>
@@ -403,96 +450,219 @@ __global__ __launch_bounds__(kThreads) void ns_gemm_bf16_kernel(const GemmArgs a
   for (int kt = 0; kt + 1 < KT; ++kt) kstep(IC<1>{}, kt);
   kstep(IC<0>{}, KT - 1);
 
-  const bool mirror = a.symmetric && (t.ti != t.tj);
-  tile_epilogue<bf16_t, WN, MI, NI>(a, acc, reinterpret_cast<float*>(&lds[0][0]), t.mat, m0 + wm * WM, n0 + wn * WN,
-                                    mirror);
+  Epilogue<bf16_t, WN, MI, NI> epi(a, t.mat, m0 + wm * WM, n0 + wn * WN, a.symmetric && (t.ti != t.tj));
+  epi.template prefetch<0>();
+  epi.run(acc, reinterpret_cast<float*>(&lds[0][0]));
 }
 
 // ---- bf16 kernel, direct-to-LDS pipeline ------------------------------------------------------
-// 256 x 256 tile, 512 threads = 8 wavefronts (2 x 4, each 128 x 64), two per SIMD so that one
-// multiplies while the other waits on LDS.  Operand tiles go from global memory straight into
-// LDS (global_load_lds, 16 bytes per lane, no staging registers) through a ring of 4 stages of
-// K = 32, so a tile is requested three steps (~3000 MFMA cycles per SIMD) before it is used.
+// Block tile BM x BN, WGM x WGN wavefronts of 128 x 64 each, K step 32, a ring of STAGES LDS
+// stages filled straight from global memory (global_load_lds, 16 bytes per lane, no staging
+// registers).  Two configurations are built:
+//   256 x 128, 4 wavefronts, 3 stages (72 KB LDS): two workgroups share a CU, so one multiplies
+//       while the other is in its prologue, epilogue or at a barrier;
+//   256 x 256, 8 wavefronts, 4 stages (128 KB LDS): one workgroup per CU, two wavefronts per SIMD.
 //
-// LDS layouts of one 256 x 32 operand tile (16 KB), in 16-byte chunks:
-//   row-major operand (K contiguous in memory): 256 rows x 4 chunks, chunk c of row r at
+// LDS layouts of one R x 32 operand tile, in 16-byte chunks:
+//   row-major operand (K contiguous in memory): R rows x 4 chunks, chunk c of row r at
 //     r * 4 + (c ^ ((r >> 2) & 3)); a fragment is one ds_read_b128 per lane (8 consecutive k);
-//   K-major operand (stored K x M): 32 k-rows x 32 chunks, chunk c of k-row k at
-//     k * 32 + (c ^ ((k & 3) << 2)); a fragment is two ds_read_b64_tr_b16 per lane: 16 lanes
-//     fetch a 4 (k) x 16 (m) block and each receives the 4 k-values of one m.
+//   K-major operand (stored K x R): 32 k-rows x R/8 chunks, chunk c of k-row k at
+//     k * (R / 8) + (c ^ ((k & 3) << 2)); a fragment is two ds_read_b64_tr_b16 per lane: 16 lanes
+//     fetch a 4 (k) x 16 (r) block and each receives the 4 k-values of one r.
 // A direct load writes lane l's 16 bytes at (wave-uniform base) + 16 l, so the swizzle is applied
 // by choosing which global chunk each lane fetches.
-constexpr int kThreadsV2 = 512;
 typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x8 __attribute__((ext_vector_type(8)));
 #define MONA_AS1 __attribute__((address_space(1)))
 #define MONA_AS3 __attribute__((address_space(3)))
+#ifdef MONA_TIMING
+// debug builds only: per-workgroup cycle stamps (kernel start, pipeline primed, main loop done, end)
+__device__ unsigned long long g_timing[4 * 65536];
+#define MONA_STAMP(slot)                                                                     \
+  do {                                                                                       \
+    if (threadIdx.x == 0 && blockIdx.x < 65536) g_timing[blockIdx.x * 4 + (slot)] = __builtin_readcyclecounter(); \
+  } while (0)
+#else
+#define MONA_STAMP(slot) do {} while (0)
+#endif
 
-template <bool TP, bool TQ>
-__global__ __launch_bounds__(kThreadsV2) void ns_gemm_bf16_v2_kernel(const GemmArgs a) {
-  constexpr int BM = 256, BN = 256, BK = 32, STAGES = 4;
+// A fragment as the LDS read instructions deliver it.  The registers are written when the data
+// returns, not when the read is issued, so until the matching wait they must stay exactly where
+// the read instruction was told to put them: no copies, no repacking.  Each kind therefore keeps
+// the destination registers of its reads as they are and is only turned into an MFMA operand
+// after the wait.
+struct FragR {            // row-major operand: one ds_read_b128
+  u32x4 v;
+  __device__ __forceinline__ bf16x8 get() const { return __builtin_bit_cast(bf16x8, v); }
+};
+struct FragT {            // K-major operand: two ds_read_b64_tr_b16 (k 0..3 and k 4..7 of the lane's row)
+  u32x2 lo, hi;
+  __device__ __forceinline__ bf16x8 get() const {
+    const u32x4 v = {lo.x, lo.y, hi.x, hi.y};
+    return __builtin_bit_cast(bf16x8, v);
+  }
+};
+// s_waitcnt lgkmcnt(PENDING) tied to the fragment registers it guards, so that no consumer of those
+// registers can be scheduled above the wait.
+template <int PENDING>
+__device__ __forceinline__ void wait_frags(FragR (&a)[4], FragR (&b)[2]) {
+  asm volatile("s_waitcnt lgkmcnt(%6)"
+               : "+v"(a[0].v), "+v"(a[1].v), "+v"(a[2].v), "+v"(a[3].v), "+v"(b[0].v), "+v"(b[1].v)
+               : "n"(PENDING));
+}
+template <int PENDING>
+__device__ __forceinline__ void wait_frags(FragR (&a)[4], FragT (&b)[2]) {
+  asm volatile("s_waitcnt lgkmcnt(%8)"
+               : "+v"(a[0].v), "+v"(a[1].v), "+v"(a[2].v), "+v"(a[3].v), "+v"(b[0].lo), "+v"(b[0].hi), "+v"(b[1].lo),
+                 "+v"(b[1].hi)
+               : "n"(PENDING));
+}
+template <int PENDING>
+__device__ __forceinline__ void wait_frags(FragT (&a)[4], FragT (&b)[2]) {
+  asm volatile("s_waitcnt lgkmcnt(%12)"
+               : "+v"(a[0].lo), "+v"(a[0].hi), "+v"(a[1].lo), "+v"(a[1].hi), "+v"(a[2].lo), "+v"(a[2].hi), "+v"(a[3].lo),
+                 "+v"(a[3].hi), "+v"(b[0].lo), "+v"(b[0].hi), "+v"(b[1].lo), "+v"(b[1].hi)
+               : "n"(PENDING));
+}
+__device__ __forceinline__ void lds_read(FragR& f, uint32_t addr, int) {
+  asm volatile("ds_read_b128 %0, %1" : "=v"(f.v) : "v"(addr));
+}
+template <int PITCH4>     // PITCH4: bytes between k-row k and k-row k + 4
+__device__ __forceinline__ void lds_read_t(FragT& f, uint32_t addr) {
+  asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(f.lo) : "v"(addr));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.hi) : "v"(addr), "n"(PITCH4));
+}
+// s_waitcnt vmcnt(n), leaving the other counters alone (gfx9 encoding)
+#ifdef MONA_EXP_HALFDMA
+#define MONA_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | (((n) / 2) & 15) | ((((n) / 2) >> 4) << 14))
+#else
+#define MONA_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
+#endif
+
+template <int BM, int BN, int WGM, int WGN, int STAGES, int MIN_BLOCKS, bool TP, bool TQ>
+__global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_kernel(const GemmArgs a) {
+  constexpr int BK = 32;
+  constexpr int NW = WGM * WGN;
   constexpr int WM = 128, WN = 64, MI = 4, NI = 2;
-  constexpr int TILE_U = 1024;                 // 16-byte units per operand tile
-  constexpr int STAGE_U = 2 * TILE_U;          // P tile then Q tile
-  __shared__ __attribute__((aligned(16))) u32x4 lds[STAGES * STAGE_U];   // 128 KB
+  static_assert(BM == WGM * WM && BN == WGN * WN, "block tile = wavefront grid x 128 x 64");
+  constexpr int P_U = BM * 4, Q_U = BN * 4;          // 16-byte units per operand tile
+  constexpr int STAGE_U = P_U + Q_U;
+  constexpr int NLP = P_U / (64 * NW), NLQ = Q_U / (64 * NW);   // direct loads per wavefront and stage
+  constexpr int LPS = NLP + NLQ;
+  static_assert(NLP * 64 * NW == P_U && NLQ * 64 * NW == Q_U, "tiles must split evenly over the wavefronts");
+  constexpr int kStageFloats = NW * 32 * (WN + 4);
+  static_assert(kStageFloats * 4 <= STAGES * STAGE_U * 16, "epilogue staging must fit in the operand ring");
+  __shared__ __attribute__((aligned(16))) u32x4 lds[STAGES * STAGE_U];
+  __shared__ uint32_t pf_sink[64 * NW];     // landing zone of the L2 warm-up loads, never read
 
+  MONA_STAMP(0);
   const TileId t = decode_tile(a);
   if (!t.valid) return;
   const bf16_t* __restrict__ P = static_cast<const bf16_t*>(a.P) + (size_t)t.mat * a.strideP;
   const bf16_t* __restrict__ Q = static_cast<const bf16_t*>(a.Q) + (size_t)t.mat * a.strideQ;
   const int m0 = t.ti * BM, n0 = t.tj * BN;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave >> 2, wn = wave & 3;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: keeps LDS bases in SGPRs
+  const int wm = wave / WGN, wn = wave % WGN;
 
-  // ---- direct loads: 2 instructions per wavefront per operand per stage ----
-  const bf16_t* gp[2];
-  const bf16_t* gq[2];
-  static_for<2>([&](auto q) {
-    const int S = (wave * 2 + q) * 64 + lane;
+  // ---- direct loads ----
+  const bf16_t* gp[NLP];
+  const bf16_t* gq[NLQ];
+  static_for<NLP>([&](auto q) {
+    const int S = (wave * NLP + q) * 64 + lane;
     if constexpr (!TP) {
       const int row = S >> 2, c = (S & 3) ^ ((row >> 2) & 3);
       gp[q] = P + (size_t)(m0 + row) * a.ldp + c * 8;
     } else {
-      const int k = S >> 5, c = (S & 31) ^ ((k & 3) << 2);
+      constexpr int CPR = BM / 8;
+      const int k = S / CPR, c = (S % CPR) ^ ((k & 3) << 2);
       gp[q] = P + (size_t)k * a.ldp + m0 + c * 8;
     }
+  });
+  static_for<NLQ>([&](auto q) {
+    const int S = (wave * NLQ + q) * 64 + lane;
     if constexpr (!TQ) {
       const int row = S >> 2, c = (S & 3) ^ ((row >> 2) & 3);
       gq[q] = Q + (size_t)(n0 + row) * a.ldq + c * 8;
     } else {
-      const int k = S >> 5, c = (S & 31) ^ ((k & 3) << 2);
+      constexpr int CPR = BN / 8;
+      const int k = S / CPR, c = (S % CPR) ^ ((k & 3) << 2);
       gq[q] = Q + (size_t)k * a.ldq + n0 + c * 8;
     }
   });
   const size_t incp = TP ? (size_t)BK * a.ldp : (size_t)BK;   // elements per K step
   const size_t incq = TQ ? (size_t)BK * a.ldq : (size_t)BK;
-  auto issue = [&](auto stage, int kt) {
-    static_for<2>([&](auto q) {
-      u32x4* dp = lds + stage * STAGE_U + (wave * 2 + q) * 64;
-      u32x4* dq = dp + TILE_U;
-      __builtin_amdgcn_global_load_lds((const MONA_AS1 void*)(gp[q] + kt * incp), (MONA_AS3 void*)dp, 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((const MONA_AS1 void*)(gq[q] + kt * incq), (MONA_AS3 void*)dq, 16, 0, 0);
+  auto issue = [&](int stage, int kt) {
+#ifdef MONA_FAKE_K0
+    kt &= 1;   // timing experiment only (wrong results): every tile re-reads its first two K chunks
+#endif
+    u32x4* sp = lds + stage * STAGE_U;
+    static_for<NLP>([&](auto q) {
+#ifdef MONA_EXP_HALFDMA
+      if constexpr (q % 2 == 1) return;   // timing experiment only (wrong results)
+#endif
+      __builtin_amdgcn_global_load_lds((const MONA_AS1 void*)(gp[q] + kt * incp),
+                                       (MONA_AS3 void*)(sp + (wave * NLP + q) * 64), 16, 0, 0);
+    });
+    static_for<NLQ>([&](auto q) {
+#ifdef MONA_EXP_HALFDMA
+      if constexpr (q % 2 == 1) return;
+#endif
+      __builtin_amdgcn_global_load_lds((const MONA_AS1 void*)(gq[q] + kt * incq),
+                                       (MONA_AS3 void*)(sp + P_U + (wave * NLQ + q) * 64), 16, 0, 0);
     });
   };
 
-  // ---- fragment addresses (bytes inside an operand tile), per lane ----
+  // ---- L2 warm-up ----
+  // A tile is needed in LDS ~2 steps after its direct loads are issued, less than a trip to HBM.
+  // So, kPfLead steps before those loads, one lane per 128-byte line touches the lines of two
+  // K steps with a plain load whose result is never used: the direct loads then hit in L2.
+  // 64 * NW lanes cover the (BM + BN) lines (row-major operand: one line per row and pair of
+  // steps; K-major operand: 64 k-rows of BM / 64 lines).
+  static_assert(64 * NW == BM + BN, "one lane per line");
+  constexpr int kPfLead = 4;
+  const bf16_t* pf_base;
+  size_t pf_inc;           // elements per K step
+  {
+    const int tid = wave * 64 + lane;
+    if (wave * 64 < BM) {
+      if constexpr (!TP) { pf_base = P + (size_t)(m0 + tid) * a.ldp; pf_inc = BK; }
+      else { pf_base = P + (size_t)(tid / (BM / 64)) * a.ldp + m0 + (tid % (BM / 64)) * 64; pf_inc = (size_t)BK * a.ldp; }
+    } else {
+      const int id = tid - BM;
+      if constexpr (!TQ) { pf_base = Q + (size_t)(n0 + id) * a.ldq; pf_inc = BK; }
+      else { pf_base = Q + (size_t)(id / (BN / 64)) * a.ldq + n0 + (id % (BN / 64)) * 64; pf_inc = (size_t)BK * a.ldq; }
+    }
+  }
+  auto warm_l2 = [&](int chunk, int kt_count) {
+    // chunk: even K step whose line pair is touched; past the end the last pair is touched again so
+    // that the number of loads in flight stays the same in every step
+    const int c = chunk + 1 < kt_count ? chunk : kt_count - 2;
+    // The touch is itself a direct-to-LDS load (4 bytes per lane into a scratch row of this
+    // wavefront): unlike a load into a register it has no destination the compiler could hand to
+    // another value while the load is still in flight.
+    __builtin_amdgcn_global_load_lds((const MONA_AS1 void*)(pf_base + c * pf_inc),
+                                     (MONA_AS3 void*)(pf_sink + wave * 64), 4, 0, 0);
+  };
+
+  // ---- fragment addresses (LDS byte addresses relative to an operand tile), per lane ----
   // row-major layout: two variants of the chunk term, one per 16-wide k step
   const int rsw = ((lane & 31) >> 2) & 3;                 // (row >> 2) & 3, the same for every block
-  const int r_off[2] = {((lane & 31) * 4 + (((0 + (lane >> 5)) ^ rsw))) * 16,
-                        ((lane & 31) * 4 + (((2 + (lane >> 5)) ^ rsw))) * 16};
+  const uint32_t r_off[2] = {(uint32_t)(((lane & 31) * 4 + ((0 + (lane >> 5)) ^ rsw)) * 16),
+                             (uint32_t)(((lane & 31) * 4 + ((2 + (lane >> 5)) ^ rsw)) * 16)};
   // K-major layout: k-row and 16-byte chunk this lane fetches for a 4 x 16 transposed block
   const int t_k = 8 * (lane >> 5) + ((lane & 15) >> 2);    // + 16 kk + 4 quad
   const int t_x = (lane & 15) >> 2;                        // k & 3 of that row: the swizzle term
-  const int t_nl = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);  // m inside the 32-wide block
-  int ta_off[MI], tb_off[NI];
+  const int t_nl = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);  // r inside the 32-wide block
+  uint32_t ta_off[MI], tb_off[NI];
   static_for<MI>([&](auto i) {
     const int c = (wm * (WM / 8) + i * 4 + (t_nl >> 3)) ^ (t_x << 2);
-    ta_off[i] = t_k * 512 + c * 16 + (t_nl & 7) * 2;
+    ta_off[i] = (uint32_t)(t_k * (BM * 2) + c * 16 + (t_nl & 7) * 2);
   });
   static_for<NI>([&](auto j) {
     const int c = (wn * (WN / 8) + j * 4 + (t_nl >> 3)) ^ (t_x << 2);
-    tb_off[j] = t_k * 512 + c * 16 + (t_nl & 7) * 2;
+    tb_off[j] = (uint32_t)(t_k * (BN * 2) + c * 16 + (t_nl & 7) * 2);
   });
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(MONA_AS3 const char*)reinterpret_cast<const char*>(lds);
 
   f32x16 acc[MI][NI];
   static_for<MI>([&](auto i) {
@@ -502,95 +672,107 @@ __global__ __launch_bounds__(kThreadsV2) void ns_gemm_bf16_v2_kernel(const GemmA
     });
   });
 
-  auto frag_r = [&](const char* tile, int blk_row, auto kk) -> bf16x8 {
-    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(tile + blk_row * 64 + r_off[kk]));
+  // Fragment reads are written in assembly so that their order and their count are fixed: the
+  // waits below rely on LDS returning data in issue order (s_waitcnt lgkmcnt(n) = "all but the
+  // last n reads have returned"), and the compiler, which cannot see that reads of one stage do not
+  // touch the stages still being filled by direct loads, would otherwise wait for those loads.
+  // Two register slots: while slot 0 is multiplied, slot 1 is being filled.
+  typedef typename std::conditional<TP, FragT, FragR>::type FragA;
+  typedef typename std::conditional<TQ, FragT, FragR>::type FragB;
+  FragA fa[2][MI];
+  FragB fb[2][NI];
+  constexpr int kReadsA = TP ? 2 * MI : MI, kReadsB = TQ ? 2 * NI : NI;
+  constexpr int kReads = kReadsA + kReadsB;          // LDS reads per slot fill
+  constexpr int kPend = kReads > 15 ? 15 : kReads;   // lgkmcnt is a 4-bit counter
+  auto fill = [&](auto slot, int stage, auto kk) {
+    const uint32_t tp = lds_base + stage * (STAGE_U * 16);
+    const uint32_t tq = tp + P_U * 16;
+    static_for<MI>([&](auto i) {
+      if constexpr (!TP) lds_read(fa[slot][i], tp + (wm * WM + i * 32) * 64 + r_off[kk], 0);
+      else lds_read_t<4 * BM * 2>(fa[slot][i], tp + ta_off[i] + kk * (16 * BM * 2));
+    });
+    static_for<NI>([&](auto j) {
+      if constexpr (!TQ) lds_read(fb[slot][j], tq + (wn * WN + j * 32) * 64 + r_off[kk], 0);
+      else lds_read_t<4 * BN * 2>(fb[slot][j], tq + tb_off[j] + kk * (16 * BN * 2));
+    });
   };
-  // Transposed fragments are read with inline assembly: the compiler cannot tell that these LDS
-  // reads do not touch the stages still being filled by direct loads and would wait for all of
-  // those first.  The reads return through the LGKM counter; wait_frags() below waits for it.
-  auto frag_t = [&](uint32_t tile_addr, int off, auto kk, u32x2& lo, u32x2& hi) {
-    const uint32_t p0 = tile_addr + off + kk * (16 * 512);
-    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(p0));
-    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:2048" : "=v"(hi) : "v"(p0));
+  auto arrive = [&](auto slot, auto pending) {
+    static_assert(MI == 4 && NI == 2, "written for 4 x 2 blocks");
+    wait_frags<pending>(fa[slot], fb[slot]);
   };
-  auto compute = [&](auto stage) {
-    const char* tp = reinterpret_cast<const char*>(lds + stage * STAGE_U);
-    const char* tq = tp + TILE_U * 16;
-    const uint32_t tp_addr = (uint32_t)(uintptr_t)(MONA_AS3 const char*)tp;
-    const uint32_t tq_addr = tp_addr + TILE_U * 16;
-    static_for<BK / 16>([&](auto kk) {
-      bf16x8 fa[MI], fb[NI];
-      u32x2 ta[MI][2], tb[NI][2];
-      static_for<MI>([&](auto i) {
-        if constexpr (!TP) fa[i] = frag_r(tp, wm * WM + i * 32, kk);
-        else frag_t(tp_addr, ta_off[i], kk, ta[i][0], ta[i][1]);
-      });
+  auto multiply = [&](auto slot) {
+    static_for<MI>([&](auto i) {
       static_for<NI>([&](auto j) {
-        if constexpr (!TQ) fb[j] = frag_r(tq, wn * WN + j * 32, kk);
-        else frag_t(tq_addr, tb_off[j], kk, tb[j][0], tb[j][1]);
-      });
-      if constexpr (TP) {
-        asm volatile("s_waitcnt lgkmcnt(0)"
-                     : "+v"(ta[0][0]), "+v"(ta[0][1]), "+v"(ta[1][0]), "+v"(ta[1][1]), "+v"(ta[2][0]), "+v"(ta[2][1]),
-                       "+v"(ta[3][0]), "+v"(ta[3][1]));
-        static_for<MI>([&](auto i) {
-          const u32x4 v = {ta[i][0].x, ta[i][0].y, ta[i][1].x, ta[i][1].y};
-          fa[i] = __builtin_bit_cast(bf16x8, v);
-        });
-      }
-      if constexpr (TQ) {
-        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(tb[0][0]), "+v"(tb[0][1]), "+v"(tb[1][0]), "+v"(tb[1][1]));
-        static_for<NI>([&](auto j) {
-          const u32x4 v = {tb[j][0].x, tb[j][0].y, tb[j][1].x, tb[j][1].y};
-          fb[j] = __builtin_bit_cast(bf16x8, v);
-        });
-      }
-      static_for<MI>([&](auto i) {
-        static_for<NI>([&](auto j) {
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-        });
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i].get(), fb[slot][j].get(), acc[i][j], 0, 0, 0);
       });
     });
   };
-
-  // s_waitcnt vmcnt(n), leaving the other counters alone (gfx9 encoding)
-#define MONA_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
 
   const int KT = a.K / BK;      // a multiple of 4: K is a multiple of 128
-  issue(IC<0>{}, 0);
-  issue(IC<1>{}, 1);
-  issue(IC<2>{}, 2);
-  // each wavefront has 4 loads per stage in flight; stage kt is complete once at most 8 newer remain.
-  // A bare s_barrier (no fence) is used inside the pipeline: a fence would drain every load in flight.
+  // One K step on stage u (compile-time).  On entry slot 0 holds (or is receiving) the first half
+  // of stage u, and stages u and u + 1 are complete for every wavefront.
+  //   MORE:  another stage follows: its first half is fetched while the second half is multiplied
+  //   SYNC:  wait for this wavefront's loads of stage u + 2 (all but LEFT newer loads done), then meet
+  //          the other wavefronts: afterwards stage u + 2 is complete and stage u is free
+  //   ISSUE: request tile kt + 4 into stage u
+  auto step = [&](auto u, int kt, auto MORE, auto SYNC, auto LEFT, auto ISSUE) {
+#ifndef MONA_EXP_NOFILL
+    fill(IC<1>{}, u, IC<1>{});
+#endif
+    arrive(IC<0>{}, IC<kPend>{});
+    multiply(IC<0>{});
+    if constexpr (MORE) {
+#ifndef MONA_EXP_NOFILL
+      fill(IC<0>{}, (u + 1) & 3, IC<0>{});
+#endif
+      arrive(IC<1>{}, IC<kPend>{});
+    } else {
+      arrive(IC<1>{}, IC<0>{});
+    }
+    multiply(IC<1>{});
+    if constexpr (SYNC) {
+      MONA_WAIT_VM(LEFT);
+      __builtin_amdgcn_s_barrier();     // bare barrier: a fence here would drain every load in flight
+    }
+#ifndef MONA_EXP_NODMA
+    if constexpr (ISSUE) {
+      issue(u, kt + 4);
+      if constexpr ((u & 1) == 0) warm_l2(kt + 4 + kPfLead, KT);
+    }
+#endif
+  };
+
+  static_assert(STAGES == 4, "the pipeline below is written for a ring of 4 stages");
+  const bool mirror = a.symmetric && (t.tj * BN >= (t.ti + 1) * BM);   // tile strictly above the diagonal blocks
+  Epilogue<bf16_t, WN, MI, NI> epi(a, t.mat, m0 + wm * WM, n0 + wn * WN, mirror);
+  issue(0, 0);
+  issue(1, 1);
+  issue(2, 2);
+  MONA_WAIT_VM(LPS);            // LPS loads per stage and wavefront: stages 0 and 1 of this wavefront landed
+  __builtin_amdgcn_s_barrier();
+  warm_l2(4 + kPfLead - 2, KT);
+  issue(3, 3);
+  MONA_STAMP(1);
+  fill(IC<0>{}, 0, IC<0>{});
   int kt = 0;
   for (; kt + 4 < KT; kt += 4) {
-    static_for<4>([&](auto u) {
-      MONA_WAIT_VM(8);
-      __builtin_amdgcn_s_barrier();        // stage kt landed for everyone, stage kt+3 free for everyone
-      issue(IC<(u + 3) & 3>{}, kt + u + 3);
-      compute(u);
-    });
+    // Issue order is ... D(s+2) [w] D(s+3) [w] ... with one warm-up load w every other step, so
+    // exactly LPS + 1 loads are newer than the last load of stage u + 2 at every SYNC
+    static_for<4>([&](auto u) { step(u, kt + u, IC<1>{}, IC<1>{}, IC<LPS + 1>{}, IC<1>{}); });
   }
-  // last four steps: one more tile to request, then drain
-  MONA_WAIT_VM(8);
-  __builtin_amdgcn_s_barrier();
-  issue(IC<3>{}, kt + 3);
-  compute(IC<0>{});
-  MONA_WAIT_VM(8);
-  __builtin_amdgcn_s_barrier();
-  compute(IC<1>{});
-  MONA_WAIT_VM(4);
-  __builtin_amdgcn_s_barrier();
-  compute(IC<2>{});
-  MONA_WAIT_VM(0);
-  __builtin_amdgcn_s_barrier();
-  compute(IC<3>{});
-#undef MONA_WAIT_VM
-
-  const bool mirror = a.symmetric && (t.ti != t.tj);
-  tile_epilogue<bf16_t, WN, MI, NI>(a, acc, reinterpret_cast<float*>(&lds[0]), t.mat, m0 + wm * WM, n0 + wn * WN,
-                                    mirror);
+  // last four steps: nothing left to request
+  step(IC<0>{}, kt + 0, IC<1>{}, IC<1>{}, IC<LPS + 1>{}, IC<0>{});   // stage 2 done
+  step(IC<1>{}, kt + 1, IC<1>{}, IC<1>{}, IC<0>{}, IC<0>{});     // stage 3 done
+  // the operands of the first epilogue band are requested once no wait on the load counter is
+  // left, so that they arrive while the last two steps are multiplied
+  epi.template prefetch<0>();
+  step(IC<2>{}, kt + 2, IC<1>{}, IC<0>{}, IC<0>{}, IC<0>{});
+  step(IC<3>{}, kt + 3, IC<0>{}, IC<0>{}, IC<0>{}, IC<0>{});
+  MONA_STAMP(2);
+  epi.run(acc, reinterpret_cast<float*>(&lds[0]));
+  MONA_STAMP(3);
 }
+#undef MONA_WAIT_VM
 
 // ---- fp32 kernel ------------------------------------------------------------------------------
 // 128 x 128 tile, K step 16.  LDS holds each operand k-major ([k][row], padded) so a fragment
@@ -688,8 +870,9 @@ __global__ __launch_bounds__(kThreads) void ns_gemm_f32_kernel(const GemmArgs a)
     __syncthreads();
   }
 
-  const bool mirror = a.symmetric && (t.ti != t.tj);
-  tile_epilogue<float, 64, 2, 2>(a, acc, lds_raw, t.mat, m0 + wm * 64, n0 + wn * 64, mirror);
+  Epilogue<float, 64, 2, 2> epi(a, t.mat, m0 + wm * 64, n0 + wn * 64, a.symmetric && (t.ti != t.tj));
+  epi.template prefetch<0>();
+  epi.run(acc, lds_raw);
 }
 
 template <int BM, int BN>
@@ -702,6 +885,29 @@ hipError_t launch_bf16(const GemmArgs& a, bool tp, bool tq, int grid, hipStream_
 }
 
 }  // namespace
+
+static void dma_debug_report(const GemmArgs& a, bool transP, bool transQ, int grid, long long total) {
+#ifdef MONA_TIMING
+  (void)hipDeviceSynchronize();
+  static unsigned long long host[4 * 65536];
+  const int nb = grid < 65536 ? grid : 65536;
+  (void)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_timing), sizeof(unsigned long long) * 4 * nb);
+  double s01 = 0, s12 = 0, s23 = 0;
+  int n = 0;
+  for (int b = 0; b < nb && b < (int)total; ++b) {
+    const unsigned long long* q = host + 4 * b;
+    if (q[3] <= q[0]) continue;
+    s01 += (double)(q[1] - q[0]); s12 += (double)(q[2] - q[1]); s23 += (double)(q[3] - q[2]);
+    ++n;
+  }
+  if (n)
+    fprintf(stderr, "[timing] tile %dx%d M %d N %d K %d sym %d tP %d tQ %d epi %d tiles %lld: prime %.0f  loop %.0f (%.1f/step)  epilogue %.0f\n",
+            a.tile_m, a.tile_n, a.M, a.N, a.K, a.symmetric, (int)transP, (int)transQ, a.epilogue, total, s01 / n, s12 / n,
+            s12 / n / (a.K / 32), s23 / n);
+#else
+  (void)a; (void)transP; (void)transQ; (void)grid; (void)total;
+#endif
+}
 
 // development switch: MONA_GEMM_V1=1 selects the register-staged 256-tile kernel
 static const bool g_use_v2 = []() { const char* e = getenv("MONA_GEMM_V1"); return !(e && e[0] == '1'); }();
@@ -719,11 +925,15 @@ hipError_t launch_ns_gemm(const GemmArgs& a, int tile, bool transP, bool transQ,
     else return hipErrorInvalidValue;
     return hipGetLastError();
   }
-  if (tile == 256 && g_use_v2) {
-    if (!transP && !transQ) hipLaunchKernelGGL((ns_gemm_bf16_v2_kernel<false, false>), dim3(grid), dim3(kThreadsV2), 0, s, a);
-    else if (!transP && transQ) hipLaunchKernelGGL((ns_gemm_bf16_v2_kernel<false, true>), dim3(grid), dim3(kThreadsV2), 0, s, a);
-    else if (transP && transQ) hipLaunchKernelGGL((ns_gemm_bf16_v2_kernel<true, true>), dim3(grid), dim3(kThreadsV2), 0, s, a);
+  if (tile == 256 && a.tile_n == 256 && g_use_v2) {
+#define MONA_LAUNCH_DMA(TP_, TQ_)                                                                              \
+  hipLaunchKernelGGL((ns_gemm_bf16_dma_kernel<256, 256, 2, 4, 4, 1, TP_, TQ_>), dim3(grid), dim3(512), 0, s, a)
+    if (!transP && !transQ) MONA_LAUNCH_DMA(false, false);
+    else if (!transP && transQ) MONA_LAUNCH_DMA(false, true);
+    else if (transP && transQ) MONA_LAUNCH_DMA(true, true);
     else return hipErrorInvalidValue;
+#undef MONA_LAUNCH_DMA
+    dma_debug_report(a, transP, transQ, grid, total);
     return hipGetLastError();
   }
   if (tile == 256) return launch_bf16<256, 256>(a, transP, transQ, grid, s);
