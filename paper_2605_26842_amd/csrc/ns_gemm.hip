@@ -552,7 +552,6 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
   constexpr int kStageFloats = NW * 32 * (WN + 4);
   static_assert(kStageFloats * 4 <= STAGES * STAGE_U * 16, "epilogue staging must fit in the operand ring");
   __shared__ __attribute__((aligned(16))) u32x4 lds[STAGES * STAGE_U];
-  __shared__ uint32_t pf_sink[64 * NW];     // landing zone of the L2 warm-up loads, never read
 
   MONA_STAMP(0);
   const TileId t = decode_tile(a);
@@ -610,38 +609,6 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
       __builtin_amdgcn_global_load_lds((const MONA_AS1 void*)(gq[q] + kt * incq),
                                        (MONA_AS3 void*)(sp + P_U + (wave * NLQ + q) * 64), 16, 0, 0);
     });
-  };
-
-  // ---- L2 warm-up ----
-  // A tile is needed in LDS ~2 steps after its direct loads are issued, less than a trip to HBM.
-  // So, kPfLead steps before those loads, one lane per 128-byte line touches the lines of two
-  // K steps with a plain load whose result is never used: the direct loads then hit in L2.
-  // 64 * NW lanes cover the (BM + BN) lines (row-major operand: one line per row and pair of
-  // steps; K-major operand: 64 k-rows of BM / 64 lines).
-  static_assert(64 * NW == BM + BN, "one lane per line");
-  constexpr int kPfLead = 4;
-  const bf16_t* pf_base;
-  size_t pf_inc;           // elements per K step
-  {
-    const int tid = wave * 64 + lane;
-    if (wave * 64 < BM) {
-      if constexpr (!TP) { pf_base = P + (size_t)(m0 + tid) * a.ldp; pf_inc = BK; }
-      else { pf_base = P + (size_t)(tid / (BM / 64)) * a.ldp + m0 + (tid % (BM / 64)) * 64; pf_inc = (size_t)BK * a.ldp; }
-    } else {
-      const int id = tid - BM;
-      if constexpr (!TQ) { pf_base = Q + (size_t)(n0 + id) * a.ldq; pf_inc = BK; }
-      else { pf_base = Q + (size_t)(id / (BN / 64)) * a.ldq + n0 + (id % (BN / 64)) * 64; pf_inc = (size_t)BK * a.ldq; }
-    }
-  }
-  auto warm_l2 = [&](int chunk, int kt_count) {
-    // chunk: even K step whose line pair is touched; past the end the last pair is touched again so
-    // that the number of loads in flight stays the same in every step
-    const int c = chunk + 1 < kt_count ? chunk : kt_count - 2;
-    // The touch is itself a direct-to-LDS load (4 bytes per lane into a scratch row of this
-    // wavefront): unlike a load into a register it has no destination the compiler could hand to
-    // another value while the load is still in flight.
-    __builtin_amdgcn_global_load_lds((const MONA_AS1 void*)(pf_base + c * pf_inc),
-                                     (MONA_AS3 void*)(pf_sink + wave * 64), 4, 0, 0);
   };
 
   // ---- fragment addresses (LDS byte addresses relative to an operand tile), per lane ----
@@ -735,10 +702,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
       __builtin_amdgcn_s_barrier();     // bare barrier: a fence here would drain every load in flight
     }
 #ifndef MONA_EXP_NODMA
-    if constexpr (ISSUE) {
-      issue(u, kt + 4);
-      if constexpr ((u & 1) == 0) warm_l2(kt + 4 + kPfLead, KT);
-    }
+    if constexpr (ISSUE) issue(u, kt + 4);
 #endif
   };
 
@@ -750,18 +714,16 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
   issue(2, 2);
   MONA_WAIT_VM(LPS);            // LPS loads per stage and wavefront: stages 0 and 1 of this wavefront landed
   __builtin_amdgcn_s_barrier();
-  warm_l2(4 + kPfLead - 2, KT);
   issue(3, 3);
   MONA_STAMP(1);
   fill(IC<0>{}, 0, IC<0>{});
   int kt = 0;
   for (; kt + 4 < KT; kt += 4) {
-    // Issue order is ... D(s+2) [w] D(s+3) [w] ... with one warm-up load w every other step, so
-    // exactly LPS + 1 loads are newer than the last load of stage u + 2 at every SYNC
-    static_for<4>([&](auto u) { step(u, kt + u, IC<1>{}, IC<1>{}, IC<LPS + 1>{}, IC<1>{}); });
+    // in flight at each SYNC: stages u + 2 and u + 3; stage u + 2 is done when LPS loads remain
+    static_for<4>([&](auto u) { step(u, kt + u, IC<1>{}, IC<1>{}, IC<LPS>{}, IC<1>{}); });
   }
   // last four steps: nothing left to request
-  step(IC<0>{}, kt + 0, IC<1>{}, IC<1>{}, IC<LPS + 1>{}, IC<0>{});   // stage 2 done
+  step(IC<0>{}, kt + 0, IC<1>{}, IC<1>{}, IC<LPS>{}, IC<0>{});   // stage 2 done (its loads precede stage 3's)
   step(IC<1>{}, kt + 1, IC<1>{}, IC<1>{}, IC<0>{}, IC<0>{});     // stage 3 done
   // the operands of the first epilogue band are requested once no wait on the load counter is
   // left, so that they arrive while the last two steps are multiplied
