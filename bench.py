@@ -95,6 +95,9 @@ def main() -> int:
     ap.add_argument("--grad-ring", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-launch", action="store_true", help="also print per-launch timings to stderr")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB elementwise copy (negation; a reference kernel of known traffic for "
+                         "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -134,6 +137,13 @@ def main() -> int:
     hpc = B.make_hparams(hp)
     plan = opt.plan_info(hp.ns_steps)
     torch.cuda.synchronize()
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        torch.neg(src, out=dst)   # reads 1 GiB, writes 1 GiB, in a kernel nothing else here launches
+        torch.cuda.synchronize()
+        del src, dst
 
     k = 0
     for _ in range(args.warmup):
@@ -189,6 +199,15 @@ def main() -> int:
     ew_bytes = plan["elementwise_bytes"]
     ew_gbs = ew_bytes / (ew_ms * 1e-3) / 1e9 if ew_ms > 0 else 0.0
 
+    # HBM bytes per launch measured with rocprofv3 counters (a committed summary, not measured here)
+    traffic_ns = traffic_ew = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{args.workload}.json")
+    if os.path.exists(tpath) and args.ns_precision == 0 and args.g_dtype == "f32" and args.state_dtype == "f32":
+        with open(tpath) as f:
+            tj = json.load(f)
+        traffic_ns = tj.get("ns_gemm_bytes_per_launch")
+        traffic_ew = tj.get("state_update_bytes_per_launch")
+
     out = {
         "metric": "MONA optimizer steps/s",
         "value": 1e3 / ms_per_step,
@@ -212,7 +231,7 @@ def main() -> int:
             "kernel": "ns_gemm (grouped Newton-Schulz products, %d launches/step)" % plan["ns_launches"],
             "bound": "mfma", "achieved": ns_tflops, "peak": peak, "unit": "TFLOP/s",
             "frac": ns_tflops / peak,
-            "traffic": None,
+            "traffic": traffic_ns,
             "flops_per_step_algorithmic": flops_sym,
             "flops_per_step_issued": plan["ns_flops_issued"],
             "flops_per_step_dense_equivalent": flops_dense,
@@ -222,6 +241,7 @@ def main() -> int:
         "elementwise": {
             "kernel": "state_update + norm_finalize", "bound": "hbm", "achieved": ew_gbs, "peak": PEAK_HBM_GBS,
             "unit": "GB/s", "frac": ew_gbs / PEAK_HBM_GBS, "bytes_per_step": ew_bytes, "ms_per_step": ew_ms,
+            "traffic": traffic_ew,
         },
         "phases_ms": {"elementwise": ew_ms, "newton_schulz": ns_ms, "separate_update": upd_ms,
                       "step_events": step_ms_events},

@@ -42,8 +42,14 @@ struct BlockWork {
   int32_t chunk;  // chunk index inside that matrix
 };
 
-constexpr int kEwThreads = 256;
-constexpr int kEwChunk = 8192;  // elements per block of the elementwise kernel
+#ifndef MONA_EW_THREADS
+#define MONA_EW_THREADS 256
+#endif
+#ifndef MONA_EW_CHUNK
+#define MONA_EW_CHUNK 4096
+#endif
+constexpr int kEwThreads = MONA_EW_THREADS;
+constexpr int kEwChunk = MONA_EW_CHUNK;  // elements per block of the elementwise kernel
 
 // ---- Newton-Schulz product kernels -------------------------------------------------
 // out = post * (beta * E + alpha * (P Q^T)),   P: M x K,  Q: N x K  (logical shapes)

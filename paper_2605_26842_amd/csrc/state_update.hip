@@ -14,16 +14,35 @@ namespace {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ f32x4 load4(const float* p) { return *reinterpret_cast<const f32x4*>(p); }
+// The state is streamed: every array is read once and written once per step and is not touched
+// again before the next step, so the accesses are marked non-temporal.
+#ifndef MONA_EW_NT
+#define MONA_EW_NT 1
+#endif
+template <typename V> __device__ __forceinline__ V stream_load(const V* p) {
+#if MONA_EW_NT
+  return __builtin_nontemporal_load(p);
+#else
+  return *p;
+#endif
+}
+template <typename V> __device__ __forceinline__ void stream_store(V* p, V v) {
+#if MONA_EW_NT
+  __builtin_nontemporal_store(v, p);
+#else
+  *p = v;
+#endif
+}
+__device__ __forceinline__ f32x4 load4(const float* p) { return stream_load(reinterpret_cast<const f32x4*>(p)); }
 __device__ __forceinline__ f32x4 load4(const bf16_t* p) {
-  bf16x4 v = *reinterpret_cast<const bf16x4*>(p);
+  bf16x4 v = stream_load(reinterpret_cast<const bf16x4*>(p));
   f32x4 r = {(float)v.x, (float)v.y, (float)v.z, (float)v.w};
   return r;
 }
-__device__ __forceinline__ void store4(float* p, f32x4 v) { *reinterpret_cast<f32x4*>(p) = v; }
+__device__ __forceinline__ void store4(float* p, f32x4 v) { stream_store(reinterpret_cast<f32x4*>(p), v); }
 __device__ __forceinline__ void store4(bf16_t* p, f32x4 v) {
   bf16x4 r = {(bf16_t)v.x, (bf16_t)v.y, (bf16_t)v.z, (bf16_t)v.w};  // round to nearest even
-  *reinterpret_cast<bf16x4*>(p) = r;
+  stream_store(reinterpret_cast<bf16x4*>(p), r);
 }
 __device__ __forceinline__ float load1(const float* p) { return *p; }
 __device__ __forceinline__ float load1(const bf16_t* p) { return (float)*p; }
