@@ -93,6 +93,8 @@ def main() -> int:
     ap.add_argument("--state-dtype", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--g-dtype", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--grad-ring", type=int, default=2)
+    ap.add_argument("--muon-only", action="store_true",
+                    help="plain Muon step (acceleration buffers untouched): the baseline of the paper's overhead figure")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-launch", action="store_true", help="also print per-launch timings to stderr")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -117,7 +119,7 @@ def main() -> int:
     torch.cuda.set_device(dev)
     workload = wl.WORKLOADS[args.workload]
     widx = list(wl.WORKLOADS).index(args.workload)
-    hp = wl.HParams()
+    hp = wl.HParams(flags=B.MONA_FLAG_MUON_ONLY if args.muon_only else 0)
     shapes = workload.shapes()
     g_dtype = torch.float32 if args.g_dtype == "f32" else torch.bfloat16
     state_dtype = torch.float32 if args.state_dtype == "f32" else torch.bfloat16
@@ -197,12 +199,15 @@ def main() -> int:
     peak = PEAK_F32_MFMA_TFLOPS if args.ns_precision == 1 else PEAK_BF16_TFLOPS
     ns_tflops = flops_sym / (ns_ms * 1e-3) / 1e12 if ns_ms > 0 else 0.0
     ew_bytes = plan["elementwise_bytes"]
+    if args.muon_only:   # G and M read, M and the working copy written
+        ew_bytes = n_elem * ((4 if args.g_dtype == "f32" else 2) + 4 + 4 + 2)
     ew_gbs = ew_bytes / (ew_ms * 1e-3) / 1e9 if ew_ms > 0 else 0.0
 
     # HBM bytes per launch measured with rocprofv3 counters (a committed summary, not measured here)
     traffic_ns = traffic_ew = None
     tpath = os.path.join(ROOT, "profiles", f"traffic_{args.workload}.json")
-    if os.path.exists(tpath) and args.ns_precision == 0 and args.g_dtype == "f32" and args.state_dtype == "f32":
+    if os.path.exists(tpath) and args.ns_precision == 0 and args.g_dtype == "f32" and args.state_dtype == "f32" \
+            and not args.muon_only:
         with open(tpath) as f:
             tj = json.load(f)
         traffic_ns = tj.get("ns_gemm_bytes_per_launch")
@@ -225,7 +230,7 @@ def main() -> int:
             "workload": args.workload, "matrices": len(shapes), "elements": n_elem,
             "param_dtype": str(workload.w_dtype).replace("torch.", ""), "grad_dtype": args.g_dtype,
             "state_dtype": args.state_dtype, "ns_steps": hp.ns_steps, "ns_precision": args.ns_precision,
-            "grad_ring": len(ring),
+            "grad_ring": len(ring), "optimizer": "muon" if args.muon_only else "mona",
         },
         "roofline": {
             "kernel": "ns_gemm (grouped Newton-Schulz products, %d launches/step)" % plan["ns_launches"],

@@ -81,6 +81,10 @@ typedef struct mona_hparams {
 /* Keep O_k = X_T readable through mona_state_view(MONA_VIEW_O) after the step (costs one
  * extra store of the matrix in the update kernel). */
 #define MONA_FLAG_KEEP_O 0x2u
+/* Plain Muon step (Sec. 3.2, Eqs. muon_momentum / muon_ns / muon_update): M_k = mu M_{k-1} + G_k;
+ * alpha and beta_a are ignored and the buffers G_{k-1} and A are neither read nor written.  This is
+ * the baseline the paper's overhead figure (App. C) compares MONA with. */
+#define MONA_FLAG_MUON_ONLY 0x4u
 
 /* Fixed when the state is built. */
 typedef struct mona_options {

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libmona.so")
 
 MONA_OK, MONA_EINVAL, MONA_ESHAPE, MONA_ENOMEM, MONA_EHIP, MONA_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 MONA_F32, MONA_BF16 = 0, 1
-MONA_FLAG_FIRST_DIFF_ZERO, MONA_FLAG_KEEP_O = 0x1, 0x2
+MONA_FLAG_FIRST_DIFF_ZERO, MONA_FLAG_KEEP_O, MONA_FLAG_MUON_ONLY = 0x1, 0x2, 0x4
 MONA_VIEW_G_PREV, MONA_VIEW_A, MONA_VIEW_M, MONA_VIEW_NORM, MONA_VIEW_O = 0, 1, 2, 3, 4
 MONA_STATUS_ZERO_NORM, MONA_STATUS_NONFINITE = 0x1, 0x2
 

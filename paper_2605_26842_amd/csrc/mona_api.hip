@@ -335,7 +335,7 @@ int check_hparams(const mona_hparams* hp) {
       !std::isfinite(hp->ns_a) || !std::isfinite(hp->ns_b) || !std::isfinite(hp->ns_c) ||
       !std::isfinite(hp->gamma_coeff) || !std::isfinite(hp->ns_eps) || hp->ns_eps < 0.0f)
     return fail(MONA_EINVAL, "hyper-parameters must be finite (and ns_eps >= 0)");
-  if (hp->flags & ~(MONA_FLAG_FIRST_DIFF_ZERO | MONA_FLAG_KEEP_O)) return fail(MONA_EINVAL, "unknown flag bits");
+  if (hp->flags & ~(MONA_FLAG_FIRST_DIFF_ZERO | MONA_FLAG_KEEP_O | MONA_FLAG_MUON_ONLY)) return fail(MONA_EINVAL, "unknown flag bits");
   return MONA_OK;
 }
 
@@ -519,7 +519,7 @@ int mona_step(mona_state* st, const mona_matrix* mats, int32_t count, const mona
   if (prof) HIP_TRY(hipEventRecord(st->ev[0], s));
 
   // Alg. 1: difference, acceleration EMA, accelerated gradient, momentum, roll; sum of squares
-  const int use_prev = !((hp->flags & MONA_FLAG_FIRST_DIFF_ZERO) && st->k == 0);
+  const int use_prev = (hp->flags & MONA_FLAG_MUON_ONLY) ? 2 : !((hp->flags & MONA_FLAG_FIRST_DIFF_ZERO) && st->k == 0);
   const int sbf = st->opt.state_dtype == MONA_BF16;
   HIP_TRY(launch_state_update(stat, dyn, blocks, partials, L.blocks_f32g, 0, sbf, hp->momentum, hp->beta_a,
                               hp->alpha, use_prev, s));

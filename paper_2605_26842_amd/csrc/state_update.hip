@@ -80,7 +80,9 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   return t;
 }
 
-template <typename GT, typename ST>
+// ACCEL = false is plain Muon (Eq. muon_momentum fed with G_k itself): the acceleration buffers
+// are neither read nor written.
+template <typename GT, typename ST, bool ACCEL>
 __global__ __launch_bounds__(kEwThreads) void state_update_kernel(
     const MatStatic* __restrict__ stat, const MatDynamic* __restrict__ dyn,
     const BlockWork* __restrict__ work, float* __restrict__ partials, Coef c) {
@@ -116,26 +118,36 @@ __global__ __launch_bounds__(kEwThreads) void state_update_kernel(
         idx[b] = (i < count) ? base + i : -1;
         if (idx[b] >= 0) {
           vg[b] = load4(g + idx[b]);
-          vp[b] = load4(gp + idx[b]);
-          va[b] = load4(ac + idx[b]);
+          if constexpr (ACCEL) {
+            vp[b] = load4(gp + idx[b]);
+            va[b] = load4(ac + idx[b]);
+          }
           vm[b] = load4(mo + idx[b]);
         }
       }
 #pragma unroll
       for (int b = 0; b < kBatch; ++b) {
         if (idx[b] >= 0) {
-          float a4[4] = {va[b].x, va[b].y, va[b].z, va[b].w};
+          float a4[4] = {0.0f, 0.0f, 0.0f, 0.0f}, p4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+          if constexpr (ACCEL) {
+            a4[0] = va[b].x; a4[1] = va[b].y; a4[2] = va[b].z; a4[3] = va[b].w;
+            p4[0] = vp[b].x; p4[1] = vp[b].y; p4[2] = vp[b].z; p4[3] = vp[b].w;
+          }
           const float g4[4] = {vg[b].x, vg[b].y, vg[b].z, vg[b].w};
-          const float p4[4] = {vp[b].x, vp[b].y, vp[b].z, vp[b].w};
           const float m4[4] = {vm[b].x, vm[b].y, vm[b].z, vm[b].w};
           float n4[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) n4[e] = mona_element(g4[e], p4[e], a4[e], m4[e], c);
+          for (int e = 0; e < 4; ++e) {
+            if constexpr (ACCEL) n4[e] = mona_element(g4[e], p4[e], a4[e], m4[e], c);
+            else n4[e] = c.mu * m4[e] + g4[e];
+          }
           const f32x4 a = {a4[0], a4[1], a4[2], a4[3]};
           const f32x4 mnew = {n4[0], n4[1], n4[2], n4[3]};
           ss += mnew.x * mnew.x + mnew.y * mnew.y + mnew.z * mnew.z + mnew.w * mnew.w;
-          store4(gp + idx[b], vg[b]);                 // G_{k-1} <- G_k
-          store4(ac + idx[b], a);
+          if constexpr (ACCEL) {
+            store4(gp + idx[b], vg[b]);               // G_{k-1} <- G_k
+            store4(ac + idx[b], a);
+          }
           store4(mo + idx[b], mnew);
           const int xo = (ldx == n) ? idx[b] : (idx[b] / n) * ldx + (idx[b] % n);
           if (xf32) store4(xf + xo, mnew); else store4(xh + xo, mnew);
@@ -145,12 +157,17 @@ __global__ __launch_bounds__(kEwThreads) void state_update_kernel(
   } else {
     for (int i = threadIdx.x; i < count; i += kEwThreads) {
       const int id = base + i;
-      float a = load1(ac + id);
       const float gv = load1(g + id);
-      const float mnew = mona_element(gv, load1(gp + id), a, mo[id], c);
+      float mnew;
+      if constexpr (ACCEL) {
+        float a = load1(ac + id);
+        mnew = mona_element(gv, load1(gp + id), a, mo[id], c);
+        store1(gp + id, gv);
+        store1(ac + id, a);
+      } else {
+        mnew = c.mu * mo[id] + gv;
+      }
       ss += mnew * mnew;
-      store1(gp + id, gv);
-      store1(ac + id, a);
       mo[id] = mnew;
       const int xo = (id / n) * ldx + (id % n);
       if (xf32) xf[xo] = mnew; else xh[xo] = (bf16_t)mnew;
@@ -233,10 +250,10 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(uint4* __restrict__ p, s
     p[i] = z;
 }
 
-template <typename GT, typename ST>
+template <typename GT, typename ST, bool ACCEL>
 hipError_t launch_su(const MatStatic* stat, const MatDynamic* dyn, const BlockWork* work, float* partials,
                      int num_blocks, Coef c, hipStream_t s) {
-  hipLaunchKernelGGL((state_update_kernel<GT, ST>), dim3(num_blocks), dim3(kEwThreads), 0, s, stat, dyn,
+  hipLaunchKernelGGL((state_update_kernel<GT, ST, ACCEL>), dim3(num_blocks), dim3(kEwThreads), 0, s, stat, dyn,
                      work, partials, c);
   return hipGetLastError();
 }
@@ -254,13 +271,17 @@ hipError_t launch_state_update(const MatStatic* stat, const MatDynamic* dyn, con
   c.beta = beta_a;
   c.one_minus_beta = 1.0f - beta_a;
   c.alpha = alpha;
-  c.use_prev = use_prev;
-  const int key = (g_bf16 ? 2 : 0) | (state_bf16 ? 1 : 0);
+  // use_prev: 0 = take D_k = 0 (first step with the first-difference flag), 1 = Alg. 1,
+  //           2 = plain Muon (acceleration buffers untouched)
+  c.use_prev = use_prev == 1;
+  const int key = (use_prev == 2 ? 4 : 0) | (g_bf16 ? 2 : 0) | (state_bf16 ? 1 : 0);
   switch (key) {
-    case 0: return launch_su<float, float>(stat, dyn, work, partials, num_blocks, c, s);
-    case 1: return launch_su<float, bf16_t>(stat, dyn, work, partials, num_blocks, c, s);
-    case 2: return launch_su<bf16_t, float>(stat, dyn, work, partials, num_blocks, c, s);
-    default: return launch_su<bf16_t, bf16_t>(stat, dyn, work, partials, num_blocks, c, s);
+    case 0: return launch_su<float, float, true>(stat, dyn, work, partials, num_blocks, c, s);
+    case 1: return launch_su<float, bf16_t, true>(stat, dyn, work, partials, num_blocks, c, s);
+    case 2: return launch_su<bf16_t, float, true>(stat, dyn, work, partials, num_blocks, c, s);
+    case 3: return launch_su<bf16_t, bf16_t, true>(stat, dyn, work, partials, num_blocks, c, s);
+    case 4: case 5: return launch_su<float, float, false>(stat, dyn, work, partials, num_blocks, c, s);
+    default: return launch_su<bf16_t, float, false>(stat, dyn, work, partials, num_blocks, c, s);
   }
 }
 

@@ -108,6 +108,29 @@ def test_first_diff_zero_flag_and_constant_gradient():
     assert np.array_equal(hist2[-1][0].W, hist3[-1][0].W)
 
 
+def test_plain_muon_flag():
+    """MONA_FLAG_MUON_ONLY: Eqs. muon_momentum / muon_ns / muon_update, acceleration buffers untouched."""
+    say("[case] muon-only flag")
+    shapes = [(160, 288), (288, 160)]
+    weights = [wl.draw_weight(s, 101 + i, torch.float32) for i, s in enumerate(shapes)]
+    streams = [wl.GradientStream(s, 111 + i) for i, s in enumerate(shapes)]
+    grads = [[st.next() for st in streams] for _ in range(3)]
+    hp = wl.HParams(flags=B.MONA_FLAG_MUON_ONLY)        # alpha = -5 is ignored
+    _, _, hist = H.run_gpu(weights, grads, hp, 0)
+    for snap in hist:
+        for i in (0, 1):
+            assert not snap[i].A.any() and not snap[i].G_prev.any()
+    # the oracle with alpha = 0 is Muon; compare M, O and the update, not A / G_prev
+    hp0 = wl.HParams(alpha=0.0)
+    ref = H.run_oracle_for(weights, grads, hp0, [0, 1])
+    for k, snap in enumerate(hist):
+        for i in (0, 1):
+            assert H.rel_max(snap[i].M, ref[i][k]["M"]) <= H.TOL_STATE
+            assert H.rel_fro(snap[i].O, ref[i][k]["O"]) <= H.TOL_NS_BF16
+            want = H.expected_update(snap[i].W_before, ref[i][k]["O"], hp0, False)
+            assert H.rel_fro(snap[i].W - snap[i].W_before, want - snap[i].W_before) <= H.TOL_NS_BF16
+
+
 def test_zero_and_nonfinite_gradients():
     say("[case] zero / nan gradients")
     shapes = [(40, 72), (72, 40), (33, 33)]
