@@ -56,19 +56,17 @@ struct TileId {
 
 // Workgroup L runs on die L % 8.  Give every die one contiguous range of the logical tile
 // order (matrix-major), so that tiles that share operands share that die's L2.
-__device__ __forceinline__ TileId decode_tile(const GemmArgs& a) {
+__device__ __forceinline__ TileId decode_logical(const GemmArgs& a, int logical, bool in_range) {
   TileId t;
   const int total = a.tiles_per_mat * a.count;
-  const int per_xcd = gridDim.x / kXcds;
-  const int logical = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
-  t.valid = logical < total;
+  t.valid = in_range && logical < total;
   t.mat = logical / a.tiles_per_mat;
   int r = logical - t.mat * a.tiles_per_mat;
   if (a.symmetric) {
     // row block ti holds the column blocks from its diagonal onwards: tj >= ratio * ti,
     // ratio = tile rows / tile columns
     int ti = 0, row = a.tiles_n;
-    while (r >= row) { r -= row; row -= a.sym_ratio; ++ti; }
+    while (r >= row && row > 0) { r -= row; row -= a.sym_ratio; ++ti; }
     t.ti = ti;
     t.tj = ti * a.sym_ratio + r;
   } else {
@@ -76,6 +74,12 @@ __device__ __forceinline__ TileId decode_tile(const GemmArgs& a) {
     t.tj = r - t.ti * a.tiles_n;
   }
   return t;
+}
+
+// One tile per workgroup: workgroup L runs on die L % 8.
+__device__ __forceinline__ TileId decode_tile(const GemmArgs& a) {
+  const int per_xcd = gridDim.x / kXcds;
+  return decode_logical(a, (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds, true);
 }
 
 // ---- LDS layout ------------------------------------------------------------------------
@@ -367,6 +371,148 @@ struct Epilogue {
   }
 };
 
+// The same epilogue for the persistent kernel below (bf16, 64-column wavefront tiles), in bands of
+// 8 rows: one 16-byte chunk per lane and band, E and parameter chunks fetched NPF bands ahead, and a
+// staging area of only 8 x 68 floats per wavefront, which leaves the rest of the LDS free for the
+// operand stages of the next tile that are being filled meanwhile.
+template <int MI, int NI, int NPF, int NPRE, bool UPD>
+struct FineEpilogue {
+  static constexpr int WN = 64, CH = 8, LDW = WN + 4, BANDS = MI * 4;
+  static constexpr int kStageFloatsPerWave = 8 * LDW;
+  static_assert(NI * 32 == WN, "wavefront tile is 64 columns wide");
+
+  const GemmArgs& a;
+  int lane, row_w0, col_w0;
+  bool mirror, update, skip_w, w_pref;
+  float post;
+  const bf16_t* __restrict__ E;
+  bf16_t* __restrict__ C;
+  int wm_real, wn_real, w_is_bf16;
+  void* wptr;
+  bf16x8 ev[NPF];
+  bf16x8 wv[UPD ? NPF : 1];    // parameter chunks, only in the launch that carries the update
+
+  __device__ __forceinline__ FineEpilogue(const GemmArgs& args) : a(args), lane(threadIdx.x & 63) {}
+
+  __device__ __forceinline__ void begin(int tmat, int row0, int col0, bool mir) {
+    row_w0 = row0; col_w0 = col0; mirror = mir;
+    const int mi = a.members ? a.members[tmat] : tmat;
+    post = 1.0f;
+    if (a.post == POST_INV) post = a.scales[mi].inv;
+    else if (a.post == POST_INV2) post = a.scales[mi].inv2;
+    E = a.E ? static_cast<const bf16_t*>(a.E) + (size_t)tmat * a.strideE : nullptr;
+    C = static_cast<bf16_t*>(a.C) + (size_t)tmat * a.strideC;
+    update = UPD;
+    wm_real = wn_real = w_is_bf16 = 0;
+    skip_w = true;
+    wptr = nullptr;
+    if constexpr (UPD) {
+      const MatStatic& ms = a.stat[mi];
+      wm_real = ms.m; wn_real = ms.n; w_is_bf16 = ms.w_dtype;
+      wptr = a.dyn[mi].w;
+      skip_w = (a.scales[mi].status & 2u) != 0;
+    }
+    w_pref = update && !skip_w && w_is_bf16 && (wn_real % CH) == 0;
+  }
+
+  // first row of band b inside the wavefront tile: MFMA block b / 4, row group b % 4
+  static __device__ __forceinline__ constexpr int band_row(int b) { return (b >> 2) * 32 + (b & 3) * 8; }
+
+  template <int BAND>
+  __device__ __forceinline__ void prefetch() {
+    constexpr int slot = BAND % NPF;
+    const int grow = row_w0 + band_row(BAND) + (lane >> 3), gcol = col_w0 + (lane & 7) * CH;
+    if (E != nullptr) ev[slot] = *reinterpret_cast<const bf16x8*>(E + (size_t)grow * a.lde + gcol);
+    if constexpr (UPD) {
+      if (w_pref && grow < wm_real && gcol + CH <= wn_real)
+        wv[slot] = *reinterpret_cast<const bf16x8*>(static_cast<const bf16_t*>(wptr) + (size_t)grow * wn_real + gcol);
+    }
+  }
+  // the first NPRE bands are requested while the last K steps are still being multiplied (few, the
+  // fragment registers are still live then); the rest of the ring at the start of run()
+  __device__ __forceinline__ void prefetch_first() {
+    static_for<NPRE>([&](auto b) { prefetch<b>(); });
+  }
+
+  // prefetch_first() must have been called.  stage: 8 x LDW floats private to this wavefront.
+  __device__ __forceinline__ void run(f32x16 (&acc)[MI][NI], float* __restrict__ stage) {
+    static_assert(NPRE <= NPF && BANDS % NPF == 0, "bands are fetched in batches of NPF");
+    // With loads and stores in flight together the load counter cannot be waited on selectively
+    // (stores retire out of order), so every wait drains everything.  Operands are therefore fetched
+    // a batch of NPF bands at a time: one memory latency per batch instead of one per band.
+    static_for<NPF - NPRE>([&](auto b) { prefetch<NPRE + b>(); });
+    static_for<BANDS>([&](auto b) {
+      constexpr int slot = b % NPF;
+      if constexpr (b > 0 && b % NPF == 0) static_for<NPF>([&](auto q) { prefetch<b + q>(); });
+      constexpr int i = b >> 2, vg = b & 3;
+      wave_sync();         // previous band fully consumed
+      static_for<NI>([&](auto j) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          stage[((lane >> 5) * 4 + e) * LDW + j * 32 + (lane & 31)] = acc[i][j][vg * 4 + e];
+      });
+      wave_sync();
+      const int r = lane >> 3, ch = lane & 7;
+      const int grow = row_w0 + band_row(b) + r, gcol = col_w0 + ch * CH;
+      float val[CH];
+      {
+        const f32x4* src = reinterpret_cast<const f32x4*>(stage + r * LDW + ch * CH);
+        const f32x4 t0 = src[0], t1 = src[1];
+        val[0] = t0.x; val[1] = t0.y; val[2] = t0.z; val[3] = t0.w;
+        val[4] = t1.x; val[5] = t1.y; val[6] = t1.z; val[7] = t1.w;
+      }
+      if (E != nullptr) {
+#pragma unroll
+        for (int e = 0; e < CH; ++e) val[e] = post * (a.alpha * val[e] + a.beta * (float)ev[slot][e]);
+      } else {
+#pragma unroll
+        for (int e = 0; e < CH; ++e) val[e] = post * (a.alpha * val[e]);
+      }
+      bf16x8 ov;
+#pragma unroll
+      for (int e = 0; e < CH; ++e) ov[e] = (bf16_t)val[e];
+      if (!update || a.store_out) *reinterpret_cast<bf16x8*>(C + (size_t)grow * a.ldc + gcol) = ov;
+      if (mirror) {
+        // keep the rounded result for the transposed store below
+        f32x4* dst = reinterpret_cast<f32x4*>(stage + r * LDW + ch * CH);
+        dst[0] = f32x4{(float)ov[0], (float)ov[1], (float)ov[2], (float)ov[3]};
+        dst[1] = f32x4{(float)ov[4], (float)ov[5], (float)ov[6], (float)ov[7]};
+      }
+      if (UPD && !skip_w && grow < wm_real) {
+        // W <- (1 - eta lambda) W - eta gamma O, O as stored in the working precision
+        const size_t wi = (size_t)grow * wn_real + gcol;
+        if (w_pref && gcol + CH <= wn_real) {
+          bf16x8 w_in = wv[UPD ? slot : 0];
+#pragma unroll
+          for (int e = 0; e < CH; ++e) w_in[e] = (bf16_t)(a.w_keep * (float)w_in[e] - a.o_scale * (float)ov[e]);
+          *reinterpret_cast<bf16x8*>(static_cast<bf16_t*>(wptr) + wi) = w_in;
+        } else {
+#pragma unroll
+          for (int e = 0; e < CH; ++e) {
+            if (gcol + e < wn_real) {
+              if (w_is_bf16) {
+                bf16_t* w = static_cast<bf16_t*>(wptr) + wi + e;
+                *w = (bf16_t)(a.w_keep * (float)*w - a.o_scale * (float)ov[e]);
+              } else {
+                float* w = static_cast<float*>(wptr) + wi + e;
+                *w = a.w_keep * *w - a.o_scale * (float)ov[e];
+              }
+            }
+          }
+        }
+      }
+      if (mirror) {
+        // transposed copy of this band: C[col][8 consecutive rows], one 16-byte store per lane
+        wave_sync();
+        bf16x8 tv;
+#pragma unroll
+        for (int e = 0; e < CH; ++e) tv[e] = (bf16_t)stage[e * LDW + lane];
+        *reinterpret_cast<bf16x8*>(C + (size_t)(col_w0 + lane) * a.ldc + row_w0 + band_row(b)) = tv;
+      }
+    });
+  }
+};
+
 // ---- bf16 kernel -----------------------------------------------------------------------------
 template <int BM, int BN, bool TP, bool TQ>
 __global__ __launch_bounds__(kThreads) void ns_gemm_bf16_kernel(const GemmArgs a) {
@@ -523,13 +669,17 @@ __device__ __forceinline__ void wait_frags(FragT (&a)[4], FragT (&b)[2]) {
                  "+v"(a[3].hi), "+v"(b[0].lo), "+v"(b[0].hi), "+v"(b[1].lo), "+v"(b[1].hi)
                : "n"(PENDING));
 }
-__device__ __forceinline__ void lds_read(FragR& f, uint32_t addr, int) {
-  asm volatile("ds_read_b128 %0, %1" : "=v"(f.v) : "v"(addr));
+// reads at (address register) + (compile-time offset, below 64 KB)
+template <int OFF>
+__device__ __forceinline__ void lds_read(FragR& f, uint32_t addr) {
+  static_assert(OFF >= 0 && OFF < 65536, "ds offset field is 16 bits");
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(f.v) : "v"(addr), "n"(OFF));
 }
-template <int PITCH4>     // PITCH4: bytes between k-row k and k-row k + 4
+template <int OFF, int PITCH4>     // PITCH4: bytes between k-row k and k-row k + 4
 __device__ __forceinline__ void lds_read_t(FragT& f, uint32_t addr) {
-  asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(f.lo) : "v"(addr));
-  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.hi) : "v"(addr), "n"(PITCH4));
+  static_assert(OFF >= 0 && OFF + PITCH4 < 65536, "ds offset field is 16 bits");
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.lo) : "v"(addr), "n"(OFF));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.hi) : "v"(addr), "n"(OFF + PITCH4));
 }
 // s_waitcnt vmcnt(n), leaving the other counters alone (gfx9 encoding)
 #ifdef MONA_EXP_HALFDMA
@@ -538,7 +688,7 @@ __device__ __forceinline__ void lds_read_t(FragT& f, uint32_t addr) {
 #define MONA_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
 #endif
 
-template <int BM, int BN, int WGM, int WGN, int STAGES, int MIN_BLOCKS, bool TP, bool TQ>
+template <int BM, int BN, int WGM, int WGN, int STAGES, int MIN_BLOCKS, bool TP, bool TQ, bool UPD>
 __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_kernel(const GemmArgs a) {
   constexpr int BK = 32;
   constexpr int NW = WGM * WGN;
@@ -554,90 +704,97 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
   __shared__ __attribute__((aligned(16))) u32x4 lds[STAGES * STAGE_U];
 
   MONA_STAMP(0);
-  const TileId t = decode_tile(a);
-  if (!t.valid) return;
-  const bf16_t* __restrict__ P = static_cast<const bf16_t*>(a.P) + (size_t)t.mat * a.strideP;
-  const bf16_t* __restrict__ Q = static_cast<const bf16_t*>(a.Q) + (size_t)t.mat * a.strideQ;
-  const int m0 = t.ti * BM, n0 = t.tj * BN;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: keeps LDS bases in SGPRs
   const int wm = wave / WGN, wn = wave % WGN;
 
-  // ---- direct loads ----
+  // ---- persistent tile walk ----
+  // Workgroup b runs on die b % 8.  Every die owns one contiguous range of the matrix-major tile
+  // order (tiles that share operand panels share that die's L2); its workgroups take the tiles of
+  // that range round by round.
+  const int total = a.tiles_per_mat * a.count;
+  const int per_xcd = (total + kXcds - 1) / kXcds;
+  const int xcd = blockIdx.x % kXcds, slot_in_xcd = blockIdx.x / kXcds, slots = gridDim.x / kXcds;
+  auto tile_at = [&](int round) -> TileId {
+    const int local = round * slots + slot_in_xcd;
+    return decode_logical(a, xcd * per_xcd + local, local < per_xcd);
+  };
+
+  // ---- direct loads: per-tile lane addresses ----
   const bf16_t* gp[NLP];
   const bf16_t* gq[NLQ];
-  static_for<NLP>([&](auto q) {
-    const int S = (wave * NLP + q) * 64 + lane;
-    if constexpr (!TP) {
-      const int row = S >> 2, c = (S & 3) ^ ((row >> 2) & 3);
-      gp[q] = P + (size_t)(m0 + row) * a.ldp + c * 8;
-    } else {
-      constexpr int CPR = BM / 8;
-      const int k = S / CPR, c = (S % CPR) ^ ((k & 3) << 2);
-      gp[q] = P + (size_t)k * a.ldp + m0 + c * 8;
-    }
-  });
-  static_for<NLQ>([&](auto q) {
-    const int S = (wave * NLQ + q) * 64 + lane;
-    if constexpr (!TQ) {
-      const int row = S >> 2, c = (S & 3) ^ ((row >> 2) & 3);
-      gq[q] = Q + (size_t)(n0 + row) * a.ldq + c * 8;
-    } else {
-      constexpr int CPR = BN / 8;
-      const int k = S / CPR, c = (S % CPR) ^ ((k & 3) << 2);
-      gq[q] = Q + (size_t)k * a.ldq + n0 + c * 8;
-    }
-  });
+  auto set_tile = [&](const TileId& t) {
+    const bf16_t* __restrict__ P = static_cast<const bf16_t*>(a.P) + (size_t)t.mat * a.strideP;
+    const bf16_t* __restrict__ Q = static_cast<const bf16_t*>(a.Q) + (size_t)t.mat * a.strideQ;
+    const int m0 = t.ti * BM, n0 = t.tj * BN;
+    static_for<NLP>([&](auto q) {
+      const int S = (wave * NLP + q) * 64 + lane;
+      if constexpr (!TP) {
+        const int row = S >> 2, c = (S & 3) ^ ((row >> 2) & 3);
+        gp[q] = P + (size_t)(m0 + row) * a.ldp + c * 8;
+      } else {
+        constexpr int CPR = BM / 8;
+        const int k = S / CPR, c = (S % CPR) ^ ((k & 3) << 2);
+        gp[q] = P + (size_t)k * a.ldp + m0 + c * 8;
+      }
+    });
+    static_for<NLQ>([&](auto q) {
+      const int S = (wave * NLQ + q) * 64 + lane;
+      if constexpr (!TQ) {
+        const int row = S >> 2, c = (S & 3) ^ ((row >> 2) & 3);
+        gq[q] = Q + (size_t)(n0 + row) * a.ldq + c * 8;
+      } else {
+        constexpr int CPR = BN / 8;
+        const int k = S / CPR, c = (S % CPR) ^ ((k & 3) << 2);
+        gq[q] = Q + (size_t)k * a.ldq + n0 + c * 8;
+      }
+    });
+  };
   const size_t incp = TP ? (size_t)BK * a.ldp : (size_t)BK;   // elements per K step
   const size_t incq = TQ ? (size_t)BK * a.ldq : (size_t)BK;
   auto issue = [&](int stage, int kt) {
-#ifdef MONA_FAKE_K0
-    kt &= 1;   // timing experiment only (wrong results): every tile re-reads its first two K chunks
-#endif
     u32x4* sp = lds + stage * STAGE_U;
     static_for<NLP>([&](auto q) {
-#ifdef MONA_EXP_HALFDMA
-      if constexpr (q % 2 == 1) return;   // timing experiment only (wrong results)
-#endif
       __builtin_amdgcn_global_load_lds((const MONA_AS1 void*)(gp[q] + kt * incp),
                                        (MONA_AS3 void*)(sp + (wave * NLP + q) * 64), 16, 0, 0);
     });
     static_for<NLQ>([&](auto q) {
-#ifdef MONA_EXP_HALFDMA
-      if constexpr (q % 2 == 1) return;
-#endif
       __builtin_amdgcn_global_load_lds((const MONA_AS1 void*)(gq[q] + kt * incq),
                                        (MONA_AS3 void*)(sp + P_U + (wave * NLQ + q) * 64), 16, 0, 0);
     });
   };
 
-  // ---- fragment addresses (LDS byte addresses relative to an operand tile), per lane ----
-  // row-major layout: two variants of the chunk term, one per 16-wide k step
+  // ---- fragment addresses, per lane ----
+  // Every read is (address register) + (compile-time offset).  The offset field holds 16 bits, so
+  // there is one set of address registers for stages 0-1 and one for stages 2-3 (64 KB apart); the
+  // stage parity, the operand (Q tiles follow P tiles), the MFMA block and the k half go in the offset.
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(MONA_AS3 const char*)reinterpret_cast<const char*>(lds);
+  static_assert(STAGE_U * 16 == 32768, "two stages per 64 KB");
+  // row-major layout: lane's row inside a 32-row block and its swizzled chunk, one variant per k half
   const int rsw = ((lane & 31) >> 2) & 3;                 // (row >> 2) & 3, the same for every block
-  const uint32_t r_off[2] = {(uint32_t)(((lane & 31) * 4 + ((0 + (lane >> 5)) ^ rsw)) * 16),
-                             (uint32_t)(((lane & 31) * 4 + ((2 + (lane >> 5)) ^ rsw)) * 16)};
+  uint32_t ra_addr[2][2], rb_addr[2][2];                  // [stage pair][k half]
   // K-major layout: k-row and 16-byte chunk this lane fetches for a 4 x 16 transposed block
   const int t_k = 8 * (lane >> 5) + ((lane & 15) >> 2);    // + 16 kk + 4 quad
   const int t_x = (lane & 15) >> 2;                        // k & 3 of that row: the swizzle term
   const int t_nl = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);  // r inside the 32-wide block
-  uint32_t ta_off[MI], tb_off[NI];
-  static_for<MI>([&](auto i) {
-    const int c = (wm * (WM / 8) + i * 4 + (t_nl >> 3)) ^ (t_x << 2);
-    ta_off[i] = (uint32_t)(t_k * (BM * 2) + c * 16 + (t_nl & 7) * 2);
-  });
-  static_for<NI>([&](auto j) {
-    const int c = (wn * (WN / 8) + j * 4 + (t_nl >> 3)) ^ (t_x << 2);
-    tb_off[j] = (uint32_t)(t_k * (BN * 2) + c * 16 + (t_nl & 7) * 2);
-  });
-  const uint32_t lds_base = (uint32_t)(uintptr_t)(MONA_AS3 const char*)reinterpret_cast<const char*>(lds);
-
-  f32x16 acc[MI][NI];
-  static_for<MI>([&](auto i) {
+  uint32_t ta_addr[2][MI], tb_addr[2][NI];                // [stage pair][block]: the swizzle permutes blocks
+  static_for<2>([&](auto h) {
+    static_for<2>([&](auto kk) {
+      const uint32_t off = (uint32_t)(((lane & 31) * 4 + ((2 * kk + (lane >> 5)) ^ rsw)) * 16);
+      ra_addr[h][kk] = lds_base + h * 65536 + wm * WM * 64 + off;
+      rb_addr[h][kk] = lds_base + h * 65536 + wn * WN * 64 + off;
+    });
+    static_for<MI>([&](auto i) {
+      const int c = (wm * (WM / 8) + i * 4 + (t_nl >> 3)) ^ (t_x << 2);
+      ta_addr[h][i] = lds_base + h * 65536 + (uint32_t)(t_k * (BM * 2) + c * 16 + (t_nl & 7) * 2);
+    });
     static_for<NI>([&](auto j) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+      const int c = (wn * (WN / 8) + j * 4 + (t_nl >> 3)) ^ (t_x << 2);
+      tb_addr[h][j] = lds_base + h * 65536 + (uint32_t)(t_k * (BN * 2) + c * 16 + (t_nl & 7) * 2);
     });
   });
+
+  f32x16 acc[MI][NI];
 
   // Fragment reads are written in assembly so that their order and their count are fixed: the
   // waits below rely on LDS returning data in issue order (s_waitcnt lgkmcnt(n) = "all but the
@@ -651,16 +808,16 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
   constexpr int kReadsA = TP ? 2 * MI : MI, kReadsB = TQ ? 2 * NI : NI;
   constexpr int kReads = kReadsA + kReadsB;          // LDS reads per slot fill
   constexpr int kPend = kReads > 15 ? 15 : kReads;   // lgkmcnt is a 4-bit counter
-  auto fill = [&](auto slot, int stage, auto kk) {
-    const uint32_t tp = lds_base + stage * (STAGE_U * 16);
-    const uint32_t tq = tp + P_U * 16;
+  auto fill = [&](auto slot, auto stage, auto kk) {
+    constexpr int h = stage >> 1;
+    constexpr int soff = (stage & 1) * 32768;
     static_for<MI>([&](auto i) {
-      if constexpr (!TP) lds_read(fa[slot][i], tp + (wm * WM + i * 32) * 64 + r_off[kk], 0);
-      else lds_read_t<4 * BM * 2>(fa[slot][i], tp + ta_off[i] + kk * (16 * BM * 2));
+      if constexpr (!TP) lds_read<soff + i * 2048>(fa[slot][i], ra_addr[h][kk]);
+      else lds_read_t<soff + kk * (16 * BM * 2), 4 * BM * 2>(fa[slot][i], ta_addr[h][i]);
     });
     static_for<NI>([&](auto j) {
-      if constexpr (!TQ) lds_read(fb[slot][j], tq + (wn * WN + j * 32) * 64 + r_off[kk], 0);
-      else lds_read_t<4 * BN * 2>(fb[slot][j], tq + tb_off[j] + kk * (16 * BN * 2));
+      if constexpr (!TQ) lds_read<soff + P_U * 16 + j * 2048>(fb[slot][j], rb_addr[h][kk]);
+      else lds_read_t<soff + P_U * 16 + kk * (16 * BN * 2), 4 * BN * 2>(fb[slot][j], tb_addr[h][j]);
     });
   };
   auto arrive = [&](auto slot, auto pending) {
@@ -681,17 +838,13 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
   //   MORE:  another stage follows: its first half is fetched while the second half is multiplied
   //   SYNC:  wait for this wavefront's loads of stage u + 2 (all but LEFT newer loads done), then meet
   //          the other wavefronts: afterwards stage u + 2 is complete and stage u is free
-  //   ISSUE: request tile kt + 4 into stage u
+  //   ISSUE: request chunk kt + 4 into stage u
   auto step = [&](auto u, int kt, auto MORE, auto SYNC, auto LEFT, auto ISSUE) {
-#ifndef MONA_EXP_NOFILL
     fill(IC<1>{}, u, IC<1>{});
-#endif
     arrive(IC<0>{}, IC<kPend>{});
     multiply(IC<0>{});
     if constexpr (MORE) {
-#ifndef MONA_EXP_NOFILL
-      fill(IC<0>{}, (u + 1) & 3, IC<0>{});
-#endif
+      fill(IC<0>{}, IC<(u + 1) & 3>{}, IC<0>{});
       arrive(IC<1>{}, IC<kPend>{});
     } else {
       arrive(IC<1>{}, IC<0>{});
@@ -701,38 +854,77 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
       MONA_WAIT_VM(LEFT);
       __builtin_amdgcn_s_barrier();     // bare barrier: a fence here would drain every load in flight
     }
-#ifndef MONA_EXP_NODMA
     if constexpr (ISSUE) issue(u, kt + 4);
-#endif
   };
 
   static_assert(STAGES == 4, "the pipeline below is written for a ring of 4 stages");
-  const bool mirror = a.symmetric && (t.tj * BN >= (t.ti + 1) * BM);   // tile strictly above the diagonal blocks
-  Epilogue<bf16_t, WN, MI, NI> epi(a, t.mat, m0 + wm * WM, n0 + wn * WN, mirror);
+  typedef FineEpilogue<MI, NI, /*batch*/ (UPD ? 4 : 8), /*early*/ 2, UPD> Epi;
+  Epi epi(a);
+  static_assert(NW * Epi::kStageFloatsPerWave * 4 <= STAGE_U * 16, "epilogue staging must fit in the last stage");
+  // epilogue staging lives in stage 3, which the next tile's early loads (stages 0..2) leave alone
+  float* const stage_f = reinterpret_cast<float*>(lds + 3 * STAGE_U) + wave * Epi::kStageFloatsPerWave;
+
+  TileId t = tile_at(0);
+  if (!t.valid) return;
+  set_tile(t);
   issue(0, 0);
   issue(1, 1);
   issue(2, 2);
-  MONA_WAIT_VM(LPS);            // LPS loads per stage and wavefront: stages 0 and 1 of this wavefront landed
-  __builtin_amdgcn_s_barrier();
-  issue(3, 3);
-  MONA_STAMP(1);
-  fill(IC<0>{}, 0, IC<0>{});
-  int kt = 0;
-  for (; kt + 4 < KT; kt += 4) {
-    // in flight at each SYNC: stages u + 2 and u + 3; stage u + 2 is done when LPS loads remain
-    static_for<4>([&](auto u) { step(u, kt + u, IC<1>{}, IC<1>{}, IC<LPS>{}, IC<1>{}); });
+  for (int round = 0;; ++round) {
+    // entry: chunks 0..2 of tile t are in flight (or landed) in stages 0..2; stage 3 is free
+    static_for<MI>([&](auto i) {
+      static_for<NI>([&](auto j) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+      });
+    });
+    epi.begin(t.mat, t.ti * BM + wm * WM, t.tj * BN + wn * WN, a.symmetric && (t.tj * BN >= (t.ti + 1) * BM));
+    // Stores of the previous epilogue may still be in flight and, unlike loads, may retire out of
+    // order: counting "all but n" is only safe once they are gone, so drain everything here (the
+    // loads of stages 0..2 were issued a whole epilogue ago).
+    MONA_WAIT_VM(0);
+    __builtin_amdgcn_s_barrier();
+    issue(3, 3);
+    MONA_STAMP(1);
+    fill(IC<0>{}, IC<0>{}, IC<0>{});
+    int kt = 0;
+    // first pass of the ring: chunk 3 is in flight alone, then the steady pattern sets in
+    if (KT > 4) {
+      step(IC<0>{}, 0, IC<1>{}, IC<1>{}, IC<LPS>{}, IC<1>{});    // stage 2 landed long ago; LPS = chunk 3 may fly
+      step(IC<1>{}, 1, IC<1>{}, IC<1>{}, IC<LPS>{}, IC<1>{});    // chunk 3 done when only chunk 4's loads remain
+      step(IC<2>{}, 2, IC<1>{}, IC<1>{}, IC<LPS>{}, IC<1>{});
+      step(IC<3>{}, 3, IC<1>{}, IC<1>{}, IC<LPS>{}, IC<1>{});
+      kt = 4;
+      for (; kt + 4 < KT; kt += 4) {
+        // in flight at each SYNC: stages u + 2 and u + 3; stage u + 2 is done when LPS loads remain
+        static_for<4>([&](auto u) { step(u, kt + u, IC<1>{}, IC<1>{}, IC<LPS>{}, IC<1>{}); });
+      }
+    }
+    // last four steps: nothing left to request
+    step(IC<0>{}, kt + 0, IC<1>{}, IC<1>{}, IC<LPS>{}, IC<0>{});   // stage 2 done (its loads precede stage 3's)
+    step(IC<1>{}, kt + 1, IC<1>{}, IC<1>{}, IC<0>{}, IC<0>{});     // stage 3 done
+    // the first epilogue bands are requested once no wait on the load counter is left, so that
+    // they arrive while the last two steps are multiplied
+    epi.prefetch_first();
+    step(IC<2>{}, kt + 2, IC<1>{}, IC<0>{}, IC<0>{}, IC<0>{});
+    step(IC<3>{}, kt + 3, IC<0>{}, IC<0>{}, IC<0>{}, IC<0>{});
+    MONA_STAMP(2);
+    // every wavefront is done with the operand stages: request the next tile's first chunks into
+    // stages 0..2 now, so that they travel while this tile's epilogue runs out of stage 3
+    const TileId next = tile_at(round + 1);
+    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wavefront's fragment reads have returned
+    __builtin_amdgcn_s_barrier();
+    if (next.valid) {
+      set_tile(next);
+      issue(0, 0);
+      issue(1, 1);
+      issue(2, 2);
+    }
+    epi.run(acc, stage_f);
+    MONA_STAMP(3);
+    if (!next.valid) break;
+    t = next;
   }
-  // last four steps: nothing left to request
-  step(IC<0>{}, kt + 0, IC<1>{}, IC<1>{}, IC<LPS>{}, IC<0>{});   // stage 2 done (its loads precede stage 3's)
-  step(IC<1>{}, kt + 1, IC<1>{}, IC<1>{}, IC<0>{}, IC<0>{});     // stage 3 done
-  // the operands of the first epilogue band are requested once no wait on the load counter is
-  // left, so that they arrive while the last two steps are multiplied
-  epi.template prefetch<0>();
-  step(IC<2>{}, kt + 2, IC<1>{}, IC<0>{}, IC<0>{}, IC<0>{});
-  step(IC<3>{}, kt + 3, IC<0>{}, IC<0>{}, IC<0>{}, IC<0>{});
-  MONA_STAMP(2);
-  epi.run(acc, reinterpret_cast<float*>(&lds[0]));
-  MONA_STAMP(3);
 }
 #undef MONA_WAIT_VM
 
@@ -888,14 +1080,28 @@ hipError_t launch_ns_gemm(const GemmArgs& a, int tile, bool transP, bool transQ,
     return hipGetLastError();
   }
   if (tile == 256 && a.tile_n == 256 && g_use_v2) {
+    // persistent: one workgroup per CU walks its share of the tiles
+    static const int num_cus = []() {
+      int dev = 0, n = 0;
+      if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < kXcds)
+        n = 256;
+      return n / kXcds * kXcds;
+    }();
+    const int pgrid = grid < num_cus ? grid : num_cus;
 #define MONA_LAUNCH_DMA(TP_, TQ_)                                                                              \
-  hipLaunchKernelGGL((ns_gemm_bf16_dma_kernel<256, 256, 2, 4, 4, 1, TP_, TQ_>), dim3(grid), dim3(512), 0, s, a)
+  do {                                                                                                         \
+    if (a.epilogue == EPI_UPDATE)                                                                              \
+      hipLaunchKernelGGL((ns_gemm_bf16_dma_kernel<256, 256, 2, 4, 4, 1, TP_, TQ_, true>), dim3(pgrid), dim3(512), 0, s, a);  \
+    else                                                                                                       \
+      hipLaunchKernelGGL((ns_gemm_bf16_dma_kernel<256, 256, 2, 4, 4, 1, TP_, TQ_, false>), dim3(pgrid), dim3(512), 0, s, a); \
+  } while (0)
     if (!transP && !transQ) MONA_LAUNCH_DMA(false, false);
     else if (!transP && transQ) MONA_LAUNCH_DMA(false, true);
-    else if (transP && transQ) MONA_LAUNCH_DMA(true, true);
+    else if (transP && transQ && a.epilogue != EPI_UPDATE)     // Gram of a tall matrix: never carries the update
+      hipLaunchKernelGGL((ns_gemm_bf16_dma_kernel<256, 256, 2, 4, 4, 1, true, true, false>), dim3(pgrid), dim3(512), 0, s, a);
     else return hipErrorInvalidValue;
 #undef MONA_LAUNCH_DMA
-    dma_debug_report(a, transP, transQ, grid, total);
+    dma_debug_report(a, transP, transQ, pgrid, total);
     return hipGetLastError();
   }
   if (tile == 256) return launch_bf16<256, 256>(a, transP, transQ, grid, s);
