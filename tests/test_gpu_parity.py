@@ -302,3 +302,37 @@ def test_large_moe_layer_sampled():
         fro2 = float((O.double() ** 2).sum())
         assert 0.45 * p <= fro2 <= 1.45 * p, (i, fro2, p)
         assert torch.isfinite(dev_w[i].float()).all()
+
+
+def test_profiling_and_plan_reports():
+    """The timing hooks the benchmark relies on: phase events, per-launch events, plan figures."""
+    say("[case] profiling hooks")
+    w = wl.WORKLOADS["moe_bank_e64"]
+    shapes = w.shapes()[:6] + w.shapes()[-6:]          # 6 tall + 6 wide 2048x1024 matrices
+    dev = "cuda:0"
+    weights = [wl.draw_weight(s, 500 + i, torch.bfloat16, dev) for i, s in enumerate(shapes)]
+    grads = [wl.GradientStream(s, 600 + i, dev).next() for i, s in enumerate(shapes)]
+    opt = B.MonaOptimizer(weights)
+    hp = wl.HParams()
+    plan = opt.plan_info(hp.ns_steps)
+    assert plan["ns_launches"] == 2 * 3 * hp.ns_steps            # two shape groups
+    n_elem = sum(a * b for a, b in shapes)
+    assert plan["elementwise_bytes"] == n_elem * 30
+    sym = sum(hp.ns_steps * (3.0 * min(s) ** 2 * max(s) + min(s) ** 3) for s in shapes)
+    dense = sum(hp.ns_steps * (4.0 * min(s) ** 2 * max(s) + 2.0 * min(s) ** 3) for s in shapes)
+    assert sym <= plan["ns_flops_issued"] <= dense               # triangle plus full diagonal tiles
+    with pytest.raises(B.MonaError):
+        opt.last_step_times()                                    # nothing profiled yet
+    opt.set_profiling(2)
+    opt.step(grads, hp)
+    t = opt.last_step_times()
+    assert all(x >= 0 for x in t) and t[3] > 0 and abs(t[0] + t[1] + t[2] - t[3]) < 0.05 * t[3] + 0.05
+    recs = opt.last_step_launches()
+    assert len(recs) == plan["ns_launches"]
+    assert sorted({r["kind"] for r in recs}) == [0, 1, 2]
+    assert abs(sum(r["flops"] for r in recs) - plan["ns_flops_issued"]) < 1e-6 * plan["ns_flops_issued"]
+    assert all(r["ms"] > 0 for r in recs)
+    opt.set_profiling(0)
+    opt.step(grads, hp)
+    torch.cuda.synchronize()
+    assert opt.step_count() == 2
