@@ -36,6 +36,21 @@ printed numeric example in the paper: "parity unpinned" beyond those pins.
 MONA-Lite (Sec. 6.3, low-precision state): `state_dtype="bf16"` rounds the
 stored G_{k-1} and A_k to bfloat16 (round-to-nearest-even) after each step's
 arithmetic, the arithmetic itself unchanged.
+
+One-buffer form of the acceleration term (`accel_form="one_buffer"`; the
+goal of Sec. 6.3's streaming variant, no stored G_{k-1}, reached by algebra
+instead of by aliasing the gradient slot).  Substituting D_k in Eq.
+alto_accel gives A_k = [beta_a A_{k-1} - (1 - beta_a) G_{k-1}] + (1 - beta_a) G_k,
+so carrying the bracket C_k is enough:
+
+    A_k     = C_k + (1 - beta_a) G_k,        C_1 = 0   (A_0 = G_0 = 0)
+    C_{k+1} = beta_a A_k - (1 - beta_a) G_k
+
+In exact arithmetic this IS Alg. 1 (pinned: both forms agree to 1e-12 in
+float64, and C_{k+1} = -(1 - beta_a)^2 sum_j beta_a^{k-j} G_j in closed form);
+the separate code path exists only to say where the bf16 rounding falls when
+the single buffer is stored in bfloat16 (on C, after each step).  beta_a must
+not change between steps in this form.
 """
 from __future__ import annotations
 
@@ -128,15 +143,18 @@ def update_scale(m: int, n: int, gamma_coeff: float = 0.2) -> float:
 class MonaOracle:
     """State {G_{k-1}, A, M} and the step of Alg. 1 for ONE matrix, float64."""
 
-    def __init__(self, shape, state_dtype: str = "f32"):
+    def __init__(self, shape, state_dtype: str = "f32", accel_form: str = "two_buffer"):
         m, n = shape
         self.shape = (int(m), int(n))
         self.G_prev = np.zeros(self.shape, dtype=np.float64)
         self.A = np.zeros(self.shape, dtype=np.float64)
         self.M = np.zeros(self.shape, dtype=np.float64)
+        self.C = np.zeros(self.shape, dtype=np.float64)   # one-buffer form only
         self.k = 0
         assert state_dtype in ("f32", "bf16")
+        assert accel_form in ("two_buffer", "one_buffer")
         self.state_dtype = state_dtype
+        self.accel_form = accel_form
         # results of the last step, kept for inspection
         self.norm = 0.0
         self.O: Optional[np.ndarray] = None
@@ -147,6 +165,17 @@ class MonaOracle:
         state roll; returns M_k."""
         G = np.asarray(G, dtype=np.float64)
         assert G.shape == self.shape
+        if self.accel_form == "one_buffer":
+            # A_k from the carried bracket; self.A and self.G_prev are kept for inspection only
+            self.A = self.C + (1.0 - hp.beta_a) * G
+            self.G_tilde = G + hp.alpha * self.A
+            self.M = hp.momentum * self.M + self.G_tilde
+            self.C = hp.beta_a * self.A - (1.0 - hp.beta_a) * G
+            if self.state_dtype == "bf16":
+                self.C = round_to_bf16(self.C)
+            self.G_prev = G.copy()
+            self.k += 1
+            return self.M
         D = G - self.G_prev
         self.A = hp.beta_a * self.A + (1.0 - hp.beta_a) * D
         self.G_tilde = G + hp.alpha * self.A

@@ -401,10 +401,58 @@ def test_run_oracle_history_and_bf16_state_variant():
 
 
 # ----------------------------------------------------------------------------
+# one-buffer form of the acceleration term: same A_k, G~_k, M_k as Alg. 1
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("beta_a,alpha,mu", [(0.9, -5.0, 0.95), (0.975, -20.0, 0.9), (0.3, 1.5, 0.5)])
+def test_one_buffer_form_equals_algorithm_one(beta_a, alpha, mu):
+    shape, K = (6, 9), 12
+    G = grad_stream(shape, 21, K)
+    hp = OracleHParams(beta_a=beta_a, alpha=alpha, momentum=mu)
+    two, one = MonaOracle(shape), MonaOracle(shape, accel_form="one_buffer")
+    for k in range(1, K + 1):
+        two.elementwise(G[k - 1], hp)
+        one.elementwise(G[k - 1], hp)
+        # against the closed form of A_k (itself pinned above), not only against the other code path
+        A_cf = np.zeros(shape)
+        for j in range(1, k + 1):
+            Gjm1 = G[j - 2] if j >= 2 else np.zeros(shape)
+            A_cf += (1 - beta_a) * beta_a ** (k - j) * (G[j - 1] - Gjm1)
+        np.testing.assert_allclose(one.A, A_cf, rtol=1e-11, atol=1e-17)
+        np.testing.assert_allclose(one.A, two.A, rtol=1e-11, atol=1e-17)
+        np.testing.assert_allclose(one.G_tilde, two.G_tilde, rtol=1e-11, atol=1e-17)
+        np.testing.assert_allclose(one.M, two.M, rtol=1e-11, atol=1e-17)
+        # carried bracket in closed form: C_{k+1} = -(1 - beta)^2 sum_{j<=k} beta^(k-j) G_j
+        C_cf = -(1 - beta_a) ** 2 * sum(beta_a ** (k - j) * G[j - 1] for j in range(1, k + 1))
+        np.testing.assert_allclose(one.C, C_cf, rtol=1e-11, atol=1e-17)
+    # a constant gradient from the start with C_1 = -(1 - beta) g (the "G_0 := G_1" start): A_k = 0
+    g = G[0]
+    o = MonaOracle(shape, accel_form="one_buffer")
+    o.C = -(1 - beta_a) * g
+    for _ in range(4):
+        o.elementwise(g, hp)
+        assert np.abs(o.A).max() <= 1e-16 * np.abs(g).max()
+    # bf16 storage rounds the carried bracket and nothing else
+    ob = MonaOracle(shape, state_dtype="bf16", accel_form="one_buffer")
+    for k in range(3):
+        ob.elementwise(G[k], hp)
+        assert np.array_equal(ob.C, orc.round_to_bf16(ob.C))
+    rel = np.abs(ob.M - MonaOracle_run(shape, G[:3], hp).M).max() / np.abs(ob.M).max()
+    assert 0 < rel < 3e-2
+
+
+def MonaOracle_run(shape, grads, hp):
+    o = MonaOracle(shape)
+    for g in grads:
+        o.elementwise(g, hp)
+    return o
+
+
+# ----------------------------------------------------------------------------
 # planted mistakes: each plausible slip in the oracle must trip a pin above
 # ----------------------------------------------------------------------------
 def _pins_pass():
     try:
+        test_one_buffer_form_equals_algorithm_one(0.9, -5.0, 0.95)
         test_ema_and_momentum_closed_forms(0.9, -5.0, 0.95)
         test_constant_gradient_pure_decay_and_zero_acceleration()
         test_newton_schulz_matches_svd_closed_form((12, 30), 5)
@@ -491,7 +539,19 @@ def test_planted_mistakes_are_caught(monkeypatch):
         self.k += 1
         return self.M
 
-    for bad in (elem_no_roll, elem_momentum_on_raw_gradient, elem_ema_damped_momentum, elem_diff_sign):
+    def elem_one_buffer_carry_without_square(self, G, hp):
+        if self.accel_form != "one_buffer":
+            return real_elem(self, G, hp)
+        G = np.asarray(G, dtype=np.float64)
+        self.A = self.C + (1 - hp.beta_a) * G
+        self.G_tilde = G + hp.alpha * self.A
+        self.M = hp.momentum * self.M + self.G_tilde
+        self.C = hp.beta_a * self.A - G            # the carried gradient term lost its (1 - beta_a)
+        self.k += 1
+        return self.M
+
+    for bad in (elem_no_roll, elem_momentum_on_raw_gradient, elem_ema_damped_momentum, elem_diff_sign,
+                elem_one_buffer_carry_without_square):
         monkeypatch.setattr(MonaOracle, "elementwise", bad)
         assert not _pins_pass(), bad.__name__
     monkeypatch.setattr(MonaOracle, "elementwise", real_elem)
