@@ -91,6 +91,9 @@ def main() -> int:
     ap.add_argument("--workload", default="moe_layer_h4096_e128")
     ap.add_argument("--ns-precision", type=int, default=0)
     ap.add_argument("--state-dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--accel-form", default="two-buffer", choices=["two-buffer", "one-buffer"],
+                    help="two-buffer: G_{k-1} and A stored as Alg. 1 writes it; one-buffer: no stored G_{k-1} "
+                         "(22 instead of 30 bytes per element in the elementwise pass)")
     ap.add_argument("--g-dtype", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--grad-ring", type=int, default=2)
     ap.add_argument("--muon-only", action="store_true",
@@ -135,7 +138,9 @@ def main() -> int:
             streams = [wl.GradientStream(s, wl.matrix_seed(widx, i), dev) for i, s in enumerate(shapes)]
         ring.append([st.next().to(g_dtype) for st in streams])
     del streams
-    opt = B.MonaOptimizer(weights, ns_precision=args.ns_precision, state_dtype=state_dtype, g_dtype=g_dtype)
+    accel_form = B.MONA_ACCEL_ONE_BUFFER if args.accel_form == "one-buffer" else B.MONA_ACCEL_TWO_BUFFER
+    opt = B.MonaOptimizer(weights, ns_precision=args.ns_precision, state_dtype=state_dtype, g_dtype=g_dtype,
+                          accel_form=accel_form)
     hpc = B.make_hparams(hp)
     plan = opt.plan_info(hp.ns_steps)
     torch.cuda.synchronize()
@@ -207,7 +212,7 @@ def main() -> int:
     traffic_ns = traffic_ew = None
     tpath = os.path.join(ROOT, "profiles", f"traffic_{args.workload}.json")
     if os.path.exists(tpath) and args.ns_precision == 0 and args.g_dtype == "f32" and args.state_dtype == "f32" \
-            and not args.muon_only:
+            and not args.muon_only and args.accel_form == "two-buffer":
         with open(tpath) as f:
             tj = json.load(f)
         traffic_ns = tj.get("ns_gemm_bytes_per_launch")
@@ -229,7 +234,7 @@ def main() -> int:
         "config": {
             "workload": args.workload, "matrices": len(shapes), "elements": n_elem,
             "param_dtype": str(workload.w_dtype).replace("torch.", ""), "grad_dtype": args.g_dtype,
-            "state_dtype": args.state_dtype, "ns_steps": hp.ns_steps, "ns_precision": args.ns_precision,
+            "state_dtype": args.state_dtype, "accel_form": args.accel_form, "ns_steps": hp.ns_steps, "ns_precision": args.ns_precision,
             "grad_ring": len(ring), "optimizer": "muon" if args.muon_only else "mona",
         },
         "roofline": {

@@ -93,8 +93,19 @@ typedef struct mona_options {
   int32_t state_dtype;  /* mona_dtype of the stored G_{k-1} and A_k: MONA_F32 (Sec. 6.3,
                            "full precision") or MONA_BF16 (the MONA-Lite variant, Sec. 6.3);
                            M_k is always fp32                                                */
-  int32_t reserved[6];  /* must be 0 */
+  int32_t accel_form;   /* how the acceleration term (Eqs. alto_diff / alto_accel) is carried:
+                           MONA_ACCEL_TWO_BUFFER (0): G_{k-1} and A_k are stored, as Alg. 1 writes it;
+                           MONA_ACCEL_ONE_BUFFER (1): only C_{k+1} = beta_a A_k - (1 - beta_a) G_k is
+                           stored and A_k = C_k + (1 - beta_a) G_k (the same A_k in exact arithmetic).
+                           No previous-gradient buffer exists -- the aim of the streaming variant of
+                           Sec. 6.3, reached without borrowing the caller's gradient slot -- and the
+                           elementwise pass moves 22 instead of 30 bytes per element.  beta_a must
+                           then stay the same from step to step (MONA_EINVAL otherwise)            */
+  int32_t reserved[5];  /* must be 0 */
 } mona_options;
+
+#define MONA_ACCEL_TWO_BUFFER 0
+#define MONA_ACCEL_ONE_BUFFER 1
 
 typedef struct mona_state mona_state;   /* opaque, HOST */
 
@@ -105,7 +116,7 @@ typedef struct mona_state mona_state;   /* opaque, HOST */
 int mona_state_size(const mona_matrix* mats, int32_t count, const mona_options* opts,
                     size_t* bytes_out);
 
-/* Alg. 1, initialisation line: lay the state {G_{k-1}, A, M} of every matrix and the
+/* Alg. 1, initialisation line: lay the state {G_{k-1}, A, M} (or {C, M}) of every matrix and the
  * Newton-Schulz workspace out in `arena`, zero it (on `stream`, which is synchronised once
  * before returning), set k = 0 and build the launch plan (same-shape matrices are grouped
  * and orthogonalised together).
@@ -132,8 +143,11 @@ typedef enum mona_view_kind {
   MONA_VIEW_A = 1,       /* A_k:     m x n, state dtype                                */
   MONA_VIEW_M = 2,       /* M_k:     m x n, fp32                                       */
   MONA_VIEW_NORM = 3,    /* ||M_k||_F of the last step: 1 x 1 fp32                      */
-  MONA_VIEW_O = 4        /* O_k of the last step (needs MONA_FLAG_KEEP_O): m x n with a
+  MONA_VIEW_O = 4,       /* O_k of the last step (needs MONA_FLAG_KEEP_O): m x n with a
                             leading dimension ld >= n, bf16 (ns_precision 0) or fp32 (1) */
+  MONA_VIEW_C = 5        /* one-buffer form only: C_{k+1}, m x n, state dtype.  There
+                            MONA_VIEW_G_PREV and MONA_VIEW_A return MONA_EUNSUPPORTED, and
+                            here MONA_VIEW_C does                                        */
 } mona_view_kind;
 
 typedef struct mona_view {
@@ -148,7 +162,7 @@ typedef struct mona_view {
 int mona_state_view(mona_state* st, int32_t i, int32_t kind, mona_view* out);
 
 /* Checkpointing.  The persistent state is one contiguous block of the arena holding
- * {G_{k-1}, A, M} of every matrix; export copies it to dst, import copies it back
+ * {G_{k-1}, A, M} (one-buffer form: {C, M}) of every matrix; export copies it to dst, import copies it back
  * (both DEVICE-to-DEVICE, asynchronous on `stream`), and the step counter travels
  * separately.  A state imported into a fresh mona_init_state of the same matrix list
  * continues bit-identically. */

@@ -20,7 +20,8 @@ LIB_PATH = os.path.join(_HERE, "libmona.so")
 MONA_OK, MONA_EINVAL, MONA_ESHAPE, MONA_ENOMEM, MONA_EHIP, MONA_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 MONA_F32, MONA_BF16 = 0, 1
 MONA_FLAG_FIRST_DIFF_ZERO, MONA_FLAG_KEEP_O, MONA_FLAG_MUON_ONLY = 0x1, 0x2, 0x4
-MONA_VIEW_G_PREV, MONA_VIEW_A, MONA_VIEW_M, MONA_VIEW_NORM, MONA_VIEW_O = 0, 1, 2, 3, 4
+MONA_VIEW_G_PREV, MONA_VIEW_A, MONA_VIEW_M, MONA_VIEW_NORM, MONA_VIEW_O, MONA_VIEW_C = 0, 1, 2, 3, 4, 5
+MONA_ACCEL_TWO_BUFFER, MONA_ACCEL_ONE_BUFFER = 0, 1
 MONA_STATUS_ZERO_NORM, MONA_STATUS_NONFINITE = 0x1, 0x2
 
 EXPORTED = (
@@ -44,7 +45,8 @@ class mona_hparams(C.Structure):
 
 
 class mona_options(C.Structure):
-    _fields_ = [("ns_precision", C.c_int32), ("state_dtype", C.c_int32), ("reserved", C.c_int32 * 6)]
+    _fields_ = [("ns_precision", C.c_int32), ("state_dtype", C.c_int32), ("accel_form", C.c_int32),
+                ("reserved", C.c_int32 * 5)]
 
 
 class mona_view(C.Structure):
@@ -176,7 +178,8 @@ class MonaOptimizer:
     """Owns the arena and the state handle for a fixed list of parameter matrices."""
 
     def __init__(self, weights: Sequence[torch.Tensor], ns_precision: int = 0,
-                 state_dtype: torch.dtype = torch.float32, g_dtype: torch.dtype = torch.float32):
+                 state_dtype: torch.dtype = torch.float32, g_dtype: torch.dtype = torch.float32,
+                 accel_form: int = MONA_ACCEL_TWO_BUFFER):
         if not weights:
             raise ValueError("need at least one matrix")
         self.lib = load_library()
@@ -186,7 +189,8 @@ class MonaOptimizer:
         self.weights = list(weights)
         self.count = len(self.weights)
         self.g_dtype = g_dtype
-        self.opts = mona_options(ns_precision, _dtype_code(state_dtype), (C.c_int32 * 6)())
+        self.opts = mona_options(ns_precision, _dtype_code(state_dtype), accel_form, (C.c_int32 * 5)())
+        self.accel_form = accel_form
         self.ns_precision = ns_precision
         self.state_dtype = state_dtype
         shapes_only = make_matrices(self.weights, None, g_dtype)
@@ -232,6 +236,7 @@ class MonaOptimizer:
 
     def g_prev(self, i): return self.view(i, MONA_VIEW_G_PREV)
     def accel(self, i): return self.view(i, MONA_VIEW_A)
+    def carry(self, i): return self.view(i, MONA_VIEW_C)
     def momentum(self, i): return self.view(i, MONA_VIEW_M)
     def norm(self, i): return self.view(i, MONA_VIEW_NORM)
     def last_o(self, i): return self.view(i, MONA_VIEW_O)

@@ -61,7 +61,8 @@ struct Group {
 
 struct Layout {
   int count = 0;
-  int ssize = 4;             // bytes per element of the stored G_{k-1}, A
+  int ssize = 4;             // bytes per element of the stored G_{k-1}, A (or C)
+  bool one_buffer = false;   // no G_{k-1}; acc_off holds C
   std::vector<size_t> gprev_off, acc_off, mom_off;
   size_t state_begin = 0, state_bytes = 0;     // persistent {G_prev, A, M}
   size_t work_begin = 0, work_bytes = 0;       // X, S, B of every group (zeroed once)
@@ -100,6 +101,8 @@ int check_opts(const mona_options* o, mona_options* out) {
   if (z.ns_precision != 0 && z.ns_precision != 1) return fail(MONA_EINVAL, "ns_precision must be 0 or 1");
   if (z.state_dtype != MONA_F32 && z.state_dtype != MONA_BF16)
     return fail(MONA_EINVAL, "state_dtype must be MONA_F32 or MONA_BF16");
+  if (z.accel_form != MONA_ACCEL_TWO_BUFFER && z.accel_form != MONA_ACCEL_ONE_BUFFER)
+    return fail(MONA_EINVAL, "accel_form must be MONA_ACCEL_TWO_BUFFER or MONA_ACCEL_ONE_BUFFER");
   for (int r : z.reserved)
     if (r != 0) return fail(MONA_EINVAL, "reserved option fields must be 0");
   *out = z;
@@ -109,6 +112,7 @@ int check_opts(const mona_options* o, mona_options* out) {
 void build_layout(const mona_matrix* mats, int count, const mona_options& opt, Layout& L) {
   L.count = count;
   L.ssize = opt.state_dtype == MONA_BF16 ? 2 : 4;
+  L.one_buffer = opt.accel_form == MONA_ACCEL_ONE_BUFFER;
   size_t off = 0;
   // persistent state, contiguous: this block is what checkpoints carry
   L.state_begin = off;
@@ -117,7 +121,8 @@ void build_layout(const mona_matrix* mats, int count, const mona_options& opt, L
   L.mom_off.resize(count);
   for (int i = 0; i < count; ++i) {
     const size_t ne = (size_t)mats[i].m * mats[i].n;
-    L.gprev_off[i] = off; off = align_up(off + ne * L.ssize);
+    L.gprev_off[i] = off;
+    if (!L.one_buffer) off = align_up(off + ne * L.ssize);
     L.acc_off[i] = off;   off = align_up(off + ne * L.ssize);
     L.mom_off[i] = off;   off = align_up(off + ne * 4);
   }
@@ -208,6 +213,7 @@ struct mona_state {
   std::vector<mona_matrix> mats;   // shapes/dtypes given at init (pointers unused)
   char* arena = nullptr;
   int64_t k = 0;
+  float last_beta_a = -1.0f;       // one-buffer form: beta_a of the previous step (< 0: none yet)
   // pinned ring for the per-step pointer table
   MatDynamic* ring[kRing] = {nullptr, nullptr, nullptr, nullptr};
   hipEvent_t ring_ev[kRing];
@@ -436,7 +442,7 @@ int mona_init_state(const mona_matrix* mats, int32_t count, const mona_options* 
     const Group& g = L.groups[L.group_of[i]];
     MatStatic& ms = stat[i];
     memset(&ms, 0, sizeof ms);
-    ms.g_prev = st->arena + L.gprev_off[i];
+    ms.g_prev = L.one_buffer ? nullptr : st->arena + L.gprev_off[i];
     ms.acc = st->arena + L.acc_off[i];
     ms.mom = reinterpret_cast<float*>(st->arena + L.mom_off[i]);
     ms.x = st->arena + g.x_off[0] + (size_t)L.rank_in_group[i] * g.x_stride * g.esize;
@@ -481,6 +487,14 @@ int mona_step(mona_state* st, const mona_matrix* mats, int32_t count, const mona
       return fail(MONA_ESHAPE, "matrix %d: shape or dtype differs from init (%d x %d vs %d x %d)", i, a.m, a.n, b.m,
                   b.n);
   }
+  const bool muon_only = (hp->flags & MONA_FLAG_MUON_ONLY) != 0;
+  if (L.one_buffer && !muon_only) {
+    // C_{k+1} was formed with the previous step's beta_a: the identity A_k = C_k + (1 - beta_a) G_k
+    // holds only if this step uses the same value
+    if (st->last_beta_a >= 0.0f && st->last_beta_a != hp->beta_a)
+      return fail(MONA_EINVAL, "one-buffer form: beta_a changed from %g to %g between steps", (double)st->last_beta_a,
+                  (double)hp->beta_a);
+  }
   hipStream_t s = static_cast<hipStream_t>(stream);
 
   // per-step pointer table
@@ -521,10 +535,12 @@ int mona_step(mona_state* st, const mona_matrix* mats, int32_t count, const mona
   // Alg. 1: difference, acceleration EMA, accelerated gradient, momentum, roll; sum of squares
   const int use_prev = (hp->flags & MONA_FLAG_MUON_ONLY) ? 2 : !((hp->flags & MONA_FLAG_FIRST_DIFF_ZERO) && st->k == 0);
   const int sbf = st->opt.state_dtype == MONA_BF16;
-  HIP_TRY(launch_state_update(stat, dyn, blocks, partials, L.blocks_f32g, 0, sbf, hp->momentum, hp->beta_a,
+  const int one = L.one_buffer ? 1 : 0;
+  HIP_TRY(launch_state_update(stat, dyn, blocks, partials, L.blocks_f32g, 0, sbf, one, hp->momentum, hp->beta_a,
                               hp->alpha, use_prev, s));
   HIP_TRY(launch_state_update(stat, dyn, blocks + L.blocks_f32g, partials + L.blocks_f32g, nblocks - L.blocks_f32g, 1,
-                              sbf, hp->momentum, hp->beta_a, hp->alpha, use_prev, s));
+                              sbf, one, hp->momentum, hp->beta_a, hp->alpha, use_prev, s));
+  if (L.one_buffer && !muon_only) st->last_beta_a = hp->beta_a;
   HIP_TRY(launch_norm_finalize(stat, partials, scales, count, hp->ns_eps, s));
   if (prof) HIP_TRY(hipEventRecord(st->ev[1], s));
 
@@ -593,8 +609,15 @@ int mona_state_view(mona_state* st, int32_t i, int32_t kind, mona_view* out) {
   const Group& g = L.groups[L.group_of[i]];
   out->rows = q.m; out->cols = q.n; out->ld = q.n;
   switch (kind) {
-    case MONA_VIEW_G_PREV: out->ptr = st->arena + L.gprev_off[i]; out->dtype = st->opt.state_dtype; break;
-    case MONA_VIEW_A: out->ptr = st->arena + L.acc_off[i]; out->dtype = st->opt.state_dtype; break;
+    case MONA_VIEW_G_PREV:
+      if (L.one_buffer) return fail(MONA_EUNSUPPORTED, "the one-buffer form stores no G_{k-1}");
+      out->ptr = st->arena + L.gprev_off[i]; out->dtype = st->opt.state_dtype; break;
+    case MONA_VIEW_A:
+      if (L.one_buffer) return fail(MONA_EUNSUPPORTED, "the one-buffer form stores C, not A (use MONA_VIEW_C)");
+      out->ptr = st->arena + L.acc_off[i]; out->dtype = st->opt.state_dtype; break;
+    case MONA_VIEW_C:
+      if (!L.one_buffer) return fail(MONA_EUNSUPPORTED, "MONA_VIEW_C exists only in the one-buffer form");
+      out->ptr = st->arena + L.acc_off[i]; out->dtype = st->opt.state_dtype; break;
     case MONA_VIEW_M: out->ptr = st->arena + L.mom_off[i]; out->dtype = MONA_F32; break;
     case MONA_VIEW_NORM:
       out->ptr = reinterpret_cast<char*>(st->at<MatScale>(L.scales_off) + i) + offsetof(MatScale, norm);
@@ -635,6 +658,7 @@ int mona_state_import(mona_state* st, const void* src, size_t src_bytes, int64_t
   HIP_TRY(hipMemcpyAsync(st->arena + st->L.state_begin, src, st->L.state_bytes, hipMemcpyDeviceToDevice,
                          static_cast<hipStream_t>(stream)));
   st->k = step_count;
+  st->last_beta_a = -1.0f;   // the checkpoint does not say which beta_a formed C
   return MONA_OK;
 }
 
@@ -717,7 +741,9 @@ int mona_plan_info(mona_state* st, int32_t ns_steps, int64_t* launches_out, doub
     const double ne = (double)st->mats[i].m * st->mats[i].n;
     const double gsz = st->mats[i].g_dtype == MONA_BF16 ? 2 : 4;
     // state pass: read G, G_prev, A, M; write G_prev, A, M and the working copy of M
-    bytes += ne * (gsz + 2 * L.ssize + 4 + 2 * L.ssize + 4 + L.groups[L.group_of[i]].esize);
+    // (one-buffer form: C in place of G_prev and A)
+    const double aux = (L.one_buffer ? 1 : 2) * L.ssize;
+    bytes += ne * (gsz + aux + 4 + aux + 4 + L.groups[L.group_of[i]].esize);
   }
   if (launches_out) *launches_out = launches;
   if (ns_flops_executed_out) *ns_flops_executed_out = flops;

@@ -10,8 +10,8 @@ typedef __bf16 bf16_t;
 
 // Static per-matrix description, uploaded once when the state is built.
 struct MatStatic {
-  void* g_prev;        // G_{k-1}, state dtype
-  void* acc;           // A_k, state dtype
+  void* g_prev;        // G_{k-1}, state dtype (NULL in the one-buffer form)
+  void* acc;           // A_k (or, in the one-buffer form, C_{k+1}), state dtype
   float* mom;          // M_k, fp32
   void* x;             // where the Newton-Schulz input (M_k, unscaled) is written: bf16 or fp32
   int32_t m, n;        // shape
@@ -86,8 +86,8 @@ struct GemmArgs {
 
 // kernels (defined in the .hip files)
 hipError_t launch_state_update(const MatStatic* stat, const MatDynamic* dyn, const BlockWork* work,
-                               float* partials, int num_blocks, int g_bf16, int state_bf16, float mu,
-                               float beta_a, float alpha, int use_prev, hipStream_t s);
+                               float* partials, int num_blocks, int g_bf16, int state_bf16, int one_buffer,
+                               float mu, float beta_a, float alpha, int use_prev, hipStream_t s);
 hipError_t launch_norm_finalize(const MatStatic* stat, const float* partials, MatScale* scales,
                                 int count, float eps, hipStream_t s);
 hipError_t launch_plain_update(const MatStatic* stat, const MatDynamic* dyn, const MatScale* scales,

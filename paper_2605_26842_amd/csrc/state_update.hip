@@ -4,7 +4,9 @@
 // read once and written once, 16 bytes per lane, so the kernel runs at HBM speed.
 //
 // Per element, with fp32 G and fp32 state: reads G, G_{k-1}, A, M (16 B), writes G_{k-1}, A, M
-// (12 B) and the bf16 copy of M that the matrix products read (2 B): 30 B.
+// (12 B) and the bf16 copy of M that the matrix products read (2 B): 30 B.  In the one-buffer form
+// (no stored G_{k-1}: the bracket C_k = beta_a A_{k-1} - (1 - beta_a) G_{k-1} is carried instead of
+// A and G_{k-1}, and A_k = C_k + (1 - beta_a) G_k) it reads G, C, M and writes C, M and the copy: 22 B.
 #include "mona_internal.h"
 
 namespace mona {
@@ -80,9 +82,20 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   return t;
 }
 
-// ACCEL = false is plain Muon (Eq. muon_momentum fed with G_k itself): the acceleration buffers
+// One element in the one-buffer form.  c holds C_k on entry and C_{k+1} on return; returns M_k.
+// With use_prev == 0 (first step, "G_0 := G_1") A_1 = 0, i.e. C_1 = -(1 - beta_a) G_1.
+__device__ __forceinline__ float mona_element_one_buffer(float g, float& cbuf, float m, const Coef& c) {
+  const float a = c.use_prev ? (cbuf + c.one_minus_beta * g) : 0.0f;   // A_k
+  const float gt = g + c.alpha * a;
+  cbuf = c.beta * a - c.one_minus_beta * g;
+  return c.mu * m + gt;
+}
+
+enum StateMode : int { MODE_MUON = 0, MODE_TWO_BUFFER = 1, MODE_ONE_BUFFER = 2 };
+
+// MODE_MUON is plain Muon (Eq. muon_momentum fed with G_k itself): the acceleration buffers
 // are neither read nor written.
-template <typename GT, typename ST, bool ACCEL>
+template <typename GT, typename ST, int MODE>
 __global__ __launch_bounds__(kEwThreads) void state_update_kernel(
     const MatStatic* __restrict__ stat, const MatDynamic* __restrict__ dyn,
     const BlockWork* __restrict__ work, float* __restrict__ partials, Coef c) {
@@ -118,10 +131,8 @@ __global__ __launch_bounds__(kEwThreads) void state_update_kernel(
         idx[b] = (i < count) ? base + i : -1;
         if (idx[b] >= 0) {
           vg[b] = load4(g + idx[b]);
-          if constexpr (ACCEL) {
-            vp[b] = load4(gp + idx[b]);
-            va[b] = load4(ac + idx[b]);
-          }
+          if constexpr (MODE == MODE_TWO_BUFFER) vp[b] = load4(gp + idx[b]);
+          if constexpr (MODE != MODE_MUON) va[b] = load4(ac + idx[b]);
           vm[b] = load4(mo + idx[b]);
         }
       }
@@ -129,25 +140,22 @@ __global__ __launch_bounds__(kEwThreads) void state_update_kernel(
       for (int b = 0; b < kBatch; ++b) {
         if (idx[b] >= 0) {
           float a4[4] = {0.0f, 0.0f, 0.0f, 0.0f}, p4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-          if constexpr (ACCEL) {
-            a4[0] = va[b].x; a4[1] = va[b].y; a4[2] = va[b].z; a4[3] = va[b].w;
-            p4[0] = vp[b].x; p4[1] = vp[b].y; p4[2] = vp[b].z; p4[3] = vp[b].w;
-          }
+          if constexpr (MODE != MODE_MUON) { a4[0] = va[b].x; a4[1] = va[b].y; a4[2] = va[b].z; a4[3] = va[b].w; }
+          if constexpr (MODE == MODE_TWO_BUFFER) { p4[0] = vp[b].x; p4[1] = vp[b].y; p4[2] = vp[b].z; p4[3] = vp[b].w; }
           const float g4[4] = {vg[b].x, vg[b].y, vg[b].z, vg[b].w};
           const float m4[4] = {vm[b].x, vm[b].y, vm[b].z, vm[b].w};
           float n4[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            if constexpr (ACCEL) n4[e] = mona_element(g4[e], p4[e], a4[e], m4[e], c);
+            if constexpr (MODE == MODE_TWO_BUFFER) n4[e] = mona_element(g4[e], p4[e], a4[e], m4[e], c);
+            else if constexpr (MODE == MODE_ONE_BUFFER) n4[e] = mona_element_one_buffer(g4[e], a4[e], m4[e], c);
             else n4[e] = c.mu * m4[e] + g4[e];
           }
           const f32x4 a = {a4[0], a4[1], a4[2], a4[3]};
           const f32x4 mnew = {n4[0], n4[1], n4[2], n4[3]};
           ss += mnew.x * mnew.x + mnew.y * mnew.y + mnew.z * mnew.z + mnew.w * mnew.w;
-          if constexpr (ACCEL) {
-            store4(gp + idx[b], vg[b]);               // G_{k-1} <- G_k
-            store4(ac + idx[b], a);
-          }
+          if constexpr (MODE == MODE_TWO_BUFFER) store4(gp + idx[b], vg[b]);   // G_{k-1} <- G_k
+          if constexpr (MODE != MODE_MUON) store4(ac + idx[b], a);              // A_k, or C_{k+1}
           store4(mo + idx[b], mnew);
           const int xo = (ldx == n) ? idx[b] : (idx[b] / n) * ldx + (idx[b] % n);
           if (xf32) store4(xf + xo, mnew); else store4(xh + xo, mnew);
@@ -159,11 +167,15 @@ __global__ __launch_bounds__(kEwThreads) void state_update_kernel(
       const int id = base + i;
       const float gv = load1(g + id);
       float mnew;
-      if constexpr (ACCEL) {
+      if constexpr (MODE == MODE_TWO_BUFFER) {
         float a = load1(ac + id);
         mnew = mona_element(gv, load1(gp + id), a, mo[id], c);
         store1(gp + id, gv);
         store1(ac + id, a);
+      } else if constexpr (MODE == MODE_ONE_BUFFER) {
+        float cb = load1(ac + id);
+        mnew = mona_element_one_buffer(gv, cb, mo[id], c);
+        store1(ac + id, cb);
       } else {
         mnew = c.mu * mo[id] + gv;
       }
@@ -250,12 +262,22 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(uint4* __restrict__ p, s
     p[i] = z;
 }
 
-template <typename GT, typename ST, bool ACCEL>
+template <typename GT, typename ST, int MODE>
 hipError_t launch_su(const MatStatic* stat, const MatDynamic* dyn, const BlockWork* work, float* partials,
                      int num_blocks, Coef c, hipStream_t s) {
-  hipLaunchKernelGGL((state_update_kernel<GT, ST, ACCEL>), dim3(num_blocks), dim3(kEwThreads), 0, s, stat, dyn,
+  hipLaunchKernelGGL((state_update_kernel<GT, ST, MODE>), dim3(num_blocks), dim3(kEwThreads), 0, s, stat, dyn,
                      work, partials, c);
   return hipGetLastError();
+}
+template <int MODE>
+hipError_t launch_su_mode(const MatStatic* stat, const MatDynamic* dyn, const BlockWork* work, float* partials,
+                          int num_blocks, int g_bf16, int state_bf16, Coef c, hipStream_t s) {
+  switch ((g_bf16 ? 2 : 0) | (state_bf16 ? 1 : 0)) {
+    case 0: return launch_su<float, float, MODE>(stat, dyn, work, partials, num_blocks, c, s);
+    case 1: return launch_su<float, bf16_t, MODE>(stat, dyn, work, partials, num_blocks, c, s);
+    case 2: return launch_su<bf16_t, float, MODE>(stat, dyn, work, partials, num_blocks, c, s);
+    default: return launch_su<bf16_t, bf16_t, MODE>(stat, dyn, work, partials, num_blocks, c, s);
+  }
 }
 
 }  // namespace
@@ -263,8 +285,8 @@ hipError_t launch_su(const MatStatic* stat, const MatDynamic* dyn, const BlockWo
 // The gradient dtype may differ between matrices: the host orders the work table by gradient
 // dtype and launches each dtype's range of blocks separately.
 hipError_t launch_state_update(const MatStatic* stat, const MatDynamic* dyn, const BlockWork* work,
-                               float* partials, int num_blocks, int g_bf16, int state_bf16, float mu,
-                               float beta_a, float alpha, int use_prev, hipStream_t s) {
+                               float* partials, int num_blocks, int g_bf16, int state_bf16, int one_buffer,
+                               float mu, float beta_a, float alpha, int use_prev, hipStream_t s) {
   if (num_blocks <= 0) return hipSuccess;
   Coef c;
   c.mu = mu;
@@ -274,15 +296,13 @@ hipError_t launch_state_update(const MatStatic* stat, const MatDynamic* dyn, con
   // use_prev: 0 = take D_k = 0 (first step with the first-difference flag), 1 = Alg. 1,
   //           2 = plain Muon (acceleration buffers untouched)
   c.use_prev = use_prev == 1;
-  const int key = (use_prev == 2 ? 4 : 0) | (g_bf16 ? 2 : 0) | (state_bf16 ? 1 : 0);
-  switch (key) {
-    case 0: return launch_su<float, float, true>(stat, dyn, work, partials, num_blocks, c, s);
-    case 1: return launch_su<float, bf16_t, true>(stat, dyn, work, partials, num_blocks, c, s);
-    case 2: return launch_su<bf16_t, float, true>(stat, dyn, work, partials, num_blocks, c, s);
-    case 3: return launch_su<bf16_t, bf16_t, true>(stat, dyn, work, partials, num_blocks, c, s);
-    case 4: case 5: return launch_su<float, float, false>(stat, dyn, work, partials, num_blocks, c, s);
-    default: return launch_su<bf16_t, float, false>(stat, dyn, work, partials, num_blocks, c, s);
+  if (use_prev == 2) {
+    // the state dtype does not matter: the acceleration buffers are not touched
+    if (g_bf16) return launch_su<bf16_t, float, MODE_MUON>(stat, dyn, work, partials, num_blocks, c, s);
+    return launch_su<float, float, MODE_MUON>(stat, dyn, work, partials, num_blocks, c, s);
   }
+  if (one_buffer) return launch_su_mode<MODE_ONE_BUFFER>(stat, dyn, work, partials, num_blocks, g_bf16, state_bf16, c, s);
+  return launch_su_mode<MODE_TWO_BUFFER>(stat, dyn, work, partials, num_blocks, g_bf16, state_bf16, c, s);
 }
 
 hipError_t launch_norm_finalize(const MatStatic* stat, const float* partials, MatScale* scales, int count,

@@ -44,8 +44,9 @@ def oracle_hp(hp: wl.HParams) -> orc.OracleHParams:
 
 @dataclasses.dataclass
 class Snapshot:
-    G_prev: np.ndarray
-    A: np.ndarray
+    G_prev: Optional[np.ndarray]   # None in the one-buffer form
+    A: Optional[np.ndarray]        # None in the one-buffer form
+    C: Optional[np.ndarray]        # carried bracket, one-buffer form only
     M: np.ndarray
     norm: float
     O: Optional[np.ndarray]
@@ -55,12 +56,12 @@ class Snapshot:
 
 def run_gpu(weights: Sequence[torch.Tensor], grads_per_step, hp: wl.HParams, ns_precision: int = 0,
             state_dtype: torch.dtype = torch.float32, watch: Optional[Sequence[int]] = None,
-            device: str = "cuda:0"):
+            device: str = "cuda:0", accel_form: int = 0):
     """Run len(grads_per_step) steps through the C ABI.  Returns (optimizer, device weights,
     history) with history[k][i] a Snapshot for every watched matrix i."""
     dev_w = [w.to(device).contiguous() for w in weights]
     opt = B.MonaOptimizer(dev_w, ns_precision=ns_precision, state_dtype=state_dtype,
-                          g_dtype=grads_per_step[0][0].dtype)
+                          g_dtype=grads_per_step[0][0].dtype, accel_form=accel_form)
     watch = list(range(len(weights))) if watch is None else list(watch)
     hp = dataclasses.replace(hp, flags=hp.flags | B.MONA_FLAG_KEEP_O)
     history = []
@@ -71,18 +72,23 @@ def run_gpu(weights: Sequence[torch.Tensor], grads_per_step, hp: wl.HParams, ns_
         torch.cuda.synchronize()
         snap = {}
         for i in watch:
-            snap[i] = Snapshot(f64(opt.g_prev(i)), f64(opt.accel(i)), f64(opt.momentum(i)),
-                               float(opt.norm(i).item()), f64(opt.last_o(i)), f64(dev_w[i]), before[i])
+            if accel_form == B.MONA_ACCEL_ONE_BUFFER:
+                gp, ac, cb = None, None, f64(opt.carry(i))
+            else:
+                gp, ac, cb = f64(opt.g_prev(i)), f64(opt.accel(i)), None
+            snap[i] = Snapshot(gp, ac, cb, f64(opt.momentum(i)), float(opt.norm(i).item()), f64(opt.last_o(i)),
+                               f64(dev_w[i]), before[i])
         history.append(snap)
     return opt, dev_w, history
 
 
-def run_oracle_for(weights, grads_per_step, hp: wl.HParams, watch, state_dtype: str = "f32"):
+def run_oracle_for(weights, grads_per_step, hp: wl.HParams, watch, state_dtype: str = "f32",
+                   accel_form: str = "two_buffer"):
     """Oracle trajectories of the watched matrices on the exact input values."""
     ohp = oracle_hp(hp)
     out = {}
     for i in watch:
-        o = orc.MonaOracle(tuple(weights[i].shape), state_dtype)
+        o = orc.MonaOracle(tuple(weights[i].shape), state_dtype, accel_form)
         snaps = []
         for grads in grads_per_step:
             o.elementwise(f64(grads[i]), ohp)
@@ -90,7 +96,7 @@ def run_oracle_for(weights, grads_per_step, hp: wl.HParams, watch, state_dtype: 
             # Gram matrix on the short side: identical to the literal form (pinned to 1e-12 in
             # test_oracle_pins), and far cheaper on tall matrices
             O = orc.newton_schulz_short_side(o.M, ohp.ns_steps, ohp.ns_a, ohp.ns_b, ohp.ns_c, ohp.ns_eps)
-            snaps.append(dict(G_prev=o.G_prev.copy(), A=o.A.copy(), M=o.M.copy(), norm=norm, O=O))
+            snaps.append(dict(G_prev=o.G_prev.copy(), A=o.A.copy(), C=o.C.copy(), M=o.M.copy(), norm=norm, O=O))
         out[i] = snaps
     return out
 
@@ -104,15 +110,15 @@ def expected_update(W_before: np.ndarray, O: np.ndarray, hp: wl.HParams, bf16_pa
 
 
 def check_history(weights, grads_per_step, hp, history, watch, ns_tol, state_tol=TOL_STATE,
-                  state_dtype: str = "f32", label: str = ""):
+                  state_dtype: str = "f32", label: str = "", accel_form: str = "two_buffer"):
     """Compare every watched matrix at every step with the oracle; returns the worst errors."""
-    ref = run_oracle_for(weights, grads_per_step, hp, watch, state_dtype)
+    ref = run_oracle_for(weights, grads_per_step, hp, watch, state_dtype, accel_form)
     worst = dict(state=0.0, norm=0.0, ns=0.0, upd=0.0)
     for k, snap in enumerate(history):
         for i in watch:
             s, r = snap[i], ref[i][k]
             tag = f"{label} step {k + 1} matrix {i} {tuple(weights[i].shape)}"
-            for name in ("G_prev", "A", "M"):
+            for name in (("C", "M") if accel_form == "one_buffer" else ("G_prev", "A", "M")):
                 e = rel_max(getattr(s, name), r[name])
                 worst["state"] = max(worst["state"], e)
                 assert e <= state_tol, f"{tag}: {name} rel max err {e:.3e} > {state_tol}"

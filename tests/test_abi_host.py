@@ -48,6 +48,11 @@ def test_state_size_accounts_for_state_and_workspace():
     assert one - lite == 2 * n * 2                      # G_prev and A stored in bf16
     f32 = B.mona_state_size(shapes((256, 512)), 1, B.mona_options(1, B.MONA_F32))
     assert f32 - one == 2 * n * 2 + 2 * 256 * 256 * 2   # fp32 working copies
+    # one-buffer form of the acceleration term: no previous-gradient array
+    single = B.mona_state_size(shapes((256, 512)), 1, B.mona_options(0, B.MONA_F32, B.MONA_ACCEL_ONE_BUFFER))
+    assert one - single == n * 4
+    single_lite = B.mona_state_size(shapes((256, 512)), 1, B.mona_options(0, B.MONA_BF16, B.MONA_ACCEL_ONE_BUFFER))
+    assert one - single_lite == n * 4 + n * 2           # 6 instead of 12 state bytes per element
     # padding: 100 x 300 works on 128 x 384 copies
     rag = B.mona_state_size(shapes((100, 300)), 1)
     assert rag >= 100 * 300 * 12 + 2 * 128 * 384 * 2 + 2 * 128 * 128 * 2
@@ -77,6 +82,11 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert rc == B.MONA_EINVAL
     rc, _ = rc_of(lib.mona_state_size, shapes((4, 4)), 1, C.byref(B.mona_options(2, 0)), C.byref(out))
     assert rc == B.MONA_EINVAL
+    rc, msg = rc_of(lib.mona_state_size, shapes((4, 4)), 1, C.byref(B.mona_options(0, 0, 2)), C.byref(out))
+    assert rc == B.MONA_EINVAL and "accel_form" in msg
+    rc, msg = rc_of(lib.mona_state_size, shapes((4, 4)), 1,
+                    C.byref(B.mona_options(0, 0, 0, (C.c_int32 * 5)(0, 0, 1, 0, 0))), C.byref(out))
+    assert rc == B.MONA_EINVAL and "reserved" in msg
     rc, _ = rc_of(lib.mona_state_size, shapes((4, 4)), 1, None, None)
     assert rc == B.MONA_EINVAL
     # init: argument errors are reported before any HIP call

@@ -187,6 +187,86 @@ def test_low_precision_state_variant():
     assert frac < 5e-3, f"{frac:.2e} of the stored A values differ from the oracle's bf16 values"
 
 
+@pytest.mark.parametrize("state_dtype", [torch.float32, torch.bfloat16])
+def test_one_buffer_form_of_the_acceleration_term(state_dtype):
+    """No stored G_{k-1}: C_{k+1} = beta_a A_k - (1 - beta_a) G_k is carried and A_k = C_k + (1 - beta_a) G_k.
+    Checked against the oracle's own one-buffer recurrence (which is pinned to Alg. 1), and against
+    the two-buffer GPU path."""
+    lite = state_dtype == torch.bfloat16
+    say("[case] one-buffer form, state", state_dtype)
+    w, weights, grads = inputs("ragged_mix", steps=4)
+    hp = wl.HParams()
+    watch = list(range(len(weights)))
+    opt, _, hist = H.run_gpu(weights, grads, hp, 0, state_dtype=state_dtype, accel_form=B.MONA_ACCEL_ONE_BUFFER)
+    worst = H.check_history(weights, grads, hp, hist, watch, H.TOL_NS_BF16, state_tol=2.0 ** -7 if lite else H.TOL_STATE,
+                            state_dtype="bf16" if lite else "f32", label="one-buffer", accel_form="one_buffer")
+    say("[worst]", worst)
+    # the views of the arrays this form does not store say so
+    for kind in (B.MONA_VIEW_G_PREV, B.MONA_VIEW_A):
+        with pytest.raises(B.MonaError) as ei:
+            opt.view(0, kind)
+        assert ei.value.code == B.MONA_EUNSUPPORTED
+    if not lite:
+        # same M_k as Alg. 1's two-buffer form on the GPU (the two differ in rounding order only),
+        # and as the float64 oracle of Alg. 1 itself
+        opt2, _, hist2 = H.run_gpu(weights, grads, hp, 0)
+        ref = H.run_oracle_for(weights, grads, hp, watch)
+        beta = float(np.float32(hp.beta_a))
+        for i in watch:
+            assert H.rel_max(hist[-1][i].M, hist2[-1][i].M) <= 2 * H.TOL_STATE
+            assert H.rel_max(hist[-1][i].M, ref[i][-1]["M"]) <= H.TOL_STATE
+            # the carried bracket is beta_a A_k - (1 - beta_a) G_k of Alg. 1's own A_k
+            want_c = beta * ref[i][-1]["A"] - (1 - beta) * H.f64(grads[-1][i])
+            assert H.rel_max(hist[-1][i].C, want_c) <= H.TOL_STATE
+        with pytest.raises(B.MonaError) as ei:
+            opt2.view(0, B.MONA_VIEW_C)
+        assert ei.value.code == B.MONA_EUNSUPPORTED
+    # beta_a must not change between steps in this form
+    dev_g = [g.to("cuda:0") for g in grads[0]]
+    with pytest.raises(B.MonaError) as ei:
+        opt.step(dev_g, dataclasses.replace(hp, beta_a=0.95))
+    assert ei.value.code == B.MONA_EINVAL and opt.step_count() == 4
+
+
+def test_one_buffer_form_first_difference_flag_and_checkpoint():
+    say("[case] one-buffer form: constant gradient with the first-difference flag; checkpoint")
+    shapes = [(96, 160), (160, 96)]
+    weights = [wl.draw_weight(s, 201 + i, torch.float32) for i, s in enumerate(shapes)]
+    g = [wl.GradientStream(s, 211 + i).next() for i, s in enumerate(shapes)]
+    hp = wl.HParams(flags=B.MONA_FLAG_FIRST_DIFF_ZERO)
+    grads = [g, g, g]
+    _, w_one, hist = H.run_gpu(weights, grads, hp, 0, accel_form=B.MONA_ACCEL_ONE_BUFFER)
+    # A_k = 0 at every step: the momentum is plain Muon's, M_k = sum_j mu^(k-j) g
+    mu = float(np.float32(hp.momentum))
+    for i in range(2):
+        want = (1 + mu + mu * mu) * H.f64(g[i])
+        assert H.rel_max(hist[-1][i].M, want) <= H.TOL_STATE
+        # and the carried bracket sits at its fixed point -(1 - beta_a) g
+        beta = float(np.float32(hp.beta_a))
+        assert H.rel_max(hist[-1][i].C, -(1 - beta) * H.f64(g[i])) <= H.TOL_STATE
+    # checkpoint: {C, M} travels, the run continues bit-identically
+    w, weights, grads = inputs("ragged_mix", steps=4)
+    hp = wl.HParams()
+    _, w_full, hist_full = H.run_gpu(weights, grads, hp, 0, accel_form=B.MONA_ACCEL_ONE_BUFFER)
+    opt_a, w_a, _ = H.run_gpu(weights, grads[:2], hp, 0, accel_form=B.MONA_ACCEL_ONE_BUFFER)
+    blob = opt_a.export_state()
+    torch.cuda.synchronize()
+    w_b = [t.clone() for t in w_a]
+    opt_b = B.MonaOptimizer(w_b, accel_form=B.MONA_ACCEL_ONE_BUFFER)
+    opt_b.import_state(blob, 2)
+    for k in (2, 3):
+        opt_b.step([x.to("cuda:0") for x in grads[k]], hp)
+    torch.cuda.synchronize()
+    for i in range(len(weights)):
+        assert torch.equal(w_b[i], w_full[i]), f"matrix {i} differs after resume"
+        assert torch.equal(opt_b.carry(i), torch.from_numpy(hist_full[-1][i].C).float().cuda())
+    # a two-buffer checkpoint does not fit a one-buffer state
+    opt_two = B.MonaOptimizer([t.clone() for t in w_a])
+    with pytest.raises(B.MonaError) as ei:
+        opt_b.import_state(opt_two.export_state(), 0)
+    assert ei.value.code == B.MONA_ESHAPE
+
+
 def test_checkpoint_round_trip_and_determinism():
     say("[case] checkpoint / determinism")
     w, weights, grads = inputs("ragged_mix", steps=4)
