@@ -206,6 +206,60 @@ int mona_last_step_launches(mona_state* st, mona_launch_time* out, int32_t max_r
 int mona_plan_info(mona_state* st, int32_t ns_steps, int64_t* launches_out,
                    double* ns_flops_executed_out, double* elementwise_bytes_out);
 
+/* ---------------------------------------------------------------------------------------
+ * AdamW for the parameters that are not matrices (Sec. 4.1, text above Alg. 1: embeddings,
+ * biases, norm gains "fall back to AdamW").  The paper prints no formula of its own; this
+ * is the published decoupled-weight-decay Adam, with m_0 = v_0 = 0 and t counted from 1:
+ *
+ *     m_t = beta1 m_{t-1} + (1 - beta1) g_t          v_t = beta2 v_{t-1} + (1 - beta2) g_t^2
+ *     w_t = w_{t-1} - eta ( (m_t / (1 - beta1^t)) / (sqrt(v_t / (1 - beta2^t)) + eps)
+ *                           + lambda w_{t-1} )
+ *
+ * Same conventions as above: the caller owns w, g, the arena and the stream; nothing here
+ * allocates device memory; all tensors of the list are updated by one fused pass.
+ * ------------------------------------------------------------------------------------- */
+typedef struct mona_vector {
+  void* w;            /* DEVICE: parameter, n contiguous elements, 16-byte aligned; in/out  */
+  const void* g;      /* DEVICE: gradient, n contiguous elements, 16-byte aligned; read     */
+  int64_t n;          /* 1 <= n <= 2^40 (any shape: the update is elementwise)              */
+  int32_t w_dtype;    /* mona_dtype; bf16 parameters are stored round-to-nearest-even       */
+  int32_t g_dtype;    /* mona_dtype                                                         */
+} mona_vector;
+
+typedef struct mona_adamw_hparams {
+  float lr;            /* eta                                   */
+  float beta1, beta2;  /* in [0, 1)                             */
+  float eps;           /* >= 0, added to sqrt(vhat)             */
+  float weight_decay;  /* lambda, decoupled, acts on w_{t-1}    */
+} mona_adamw_hparams;
+
+typedef struct mona_adamw_state mona_adamw_state;   /* opaque, HOST */
+
+/* Bytes of DEVICE arena for the moments {m, v} (fp32) of `count` tensors plus small tables.
+ * Host-only.  vecs HOST (w / g ignored, may be NULL); bytes_out HOST. */
+int mona_adamw_state_size(const mona_vector* vecs, int32_t count, size_t* bytes_out);
+/* Lays {m, v} out in `arena` (DEVICE, 256-byte aligned, stays the caller's), zeroes them on
+ * `stream` (synchronised once before returning) and sets t = 0. */
+int mona_adamw_init_state(const mona_vector* vecs, int32_t count, void* arena, size_t arena_bytes,
+                          void* stream, mona_adamw_state** out);
+/* One AdamW step for every tensor, enqueued on `stream`, no wait.  Sizes and dtypes must
+ * match init (MONA_ESHAPE otherwise); w and g pointers may change from step to step. */
+int mona_adamw_step(mona_adamw_state* st, const mona_vector* vecs, int32_t count,
+                    const mona_adamw_hparams* hp, void* stream);
+int mona_adamw_free_state(mona_adamw_state* st);
+
+#define MONA_ADAMW_VIEW_M 0
+#define MONA_ADAMW_VIEW_V 1
+/* DEVICE address (inside the arena) and element count of tensor i's fp32 m or v. */
+int mona_adamw_state_view(mona_adamw_state* st, int32_t i, int32_t kind, void** dev_ptr,
+                          int64_t* n_out);
+/* Checkpointing: {m, v} of every tensor is one contiguous block; t travels separately. */
+int mona_adamw_state_export_size(mona_adamw_state* st, size_t* bytes_out);
+int mona_adamw_state_export(mona_adamw_state* st, void* dst, size_t dst_bytes, void* stream);
+int mona_adamw_state_import(mona_adamw_state* st, const void* src, size_t src_bytes,
+                            int64_t step_count, void* stream);
+int mona_adamw_state_step_count(mona_adamw_state* st, int64_t* t_out);
+
 const char* mona_last_error(void);
 const char* mona_version(void);
 

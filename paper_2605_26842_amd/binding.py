@@ -29,7 +29,20 @@ EXPORTED = (
     "mona_state_export_size", "mona_state_export", "mona_state_import", "mona_state_step_count",
     "mona_state_status", "mona_set_profiling", "mona_last_step_times", "mona_last_step_launches",
     "mona_plan_info", "mona_last_error", "mona_version",
+    "mona_adamw_state_size", "mona_adamw_init_state", "mona_adamw_step", "mona_adamw_free_state",
+    "mona_adamw_state_view", "mona_adamw_state_export_size", "mona_adamw_state_export",
+    "mona_adamw_state_import", "mona_adamw_state_step_count",
 )
+MONA_ADAMW_VIEW_M, MONA_ADAMW_VIEW_V = 0, 1
+
+
+class mona_vector(C.Structure):
+    _fields_ = [("w", C.c_void_p), ("g", C.c_void_p), ("n", C.c_int64), ("w_dtype", C.c_int32), ("g_dtype", C.c_int32)]
+
+
+class mona_adamw_hparams(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("weight_decay", C.c_float)]
 
 
 class mona_matrix(C.Structure):
@@ -92,6 +105,15 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.mona_state_import.argtypes = [vp, vp, sz, i64, vp]
     lib.mona_state_step_count.argtypes = [vp, P(i64)]
     lib.mona_state_status.argtypes = [vp, P(C.c_uint32), i32, vp]
+    lib.mona_adamw_state_size.argtypes = [P(mona_vector), i32, P(sz)]
+    lib.mona_adamw_init_state.argtypes = [P(mona_vector), i32, vp, sz, vp, P(vp)]
+    lib.mona_adamw_step.argtypes = [vp, P(mona_vector), i32, P(mona_adamw_hparams), vp]
+    lib.mona_adamw_free_state.argtypes = [vp]
+    lib.mona_adamw_state_view.argtypes = [vp, i32, i32, P(vp), P(i64)]
+    lib.mona_adamw_state_export_size.argtypes = [vp, P(sz)]
+    lib.mona_adamw_state_export.argtypes = [vp, vp, sz, vp]
+    lib.mona_adamw_state_import.argtypes = [vp, vp, sz, i64, vp]
+    lib.mona_adamw_state_step_count.argtypes = [vp, P(i64)]
     lib.mona_set_profiling.argtypes = [vp, i32]
     lib.mona_last_step_times.argtypes = [vp, P(C.c_float)]
     lib.mona_last_step_launches.argtypes = [vp, P(mona_launch_time), i32, P(i32)]
@@ -282,3 +304,95 @@ class MonaOptimizer:
         launches, flops, nbytes = C.c_int64(0), C.c_double(0), C.c_double(0)
         _check(self.lib.mona_plan_info(self.state, ns_steps, C.byref(launches), C.byref(flops), C.byref(nbytes)))
         return dict(ns_launches=launches.value, ns_flops_issued=flops.value, elementwise_bytes=nbytes.value)
+
+
+# ---- AdamW for the parameters that are not matrices ----------------------------------------
+def make_vectors(params: Sequence[torch.Tensor], grads: Optional[Sequence[torch.Tensor]] = None,
+                 g_dtype: torch.dtype = torch.float32):
+    """Array of mona_vector descriptors for contiguous tensors of any shape."""
+    arr = (mona_vector * len(params))()
+    for i, w in enumerate(params):
+        if not w.is_contiguous():
+            raise ValueError(f"tensor {i}: parameters must be contiguous")
+        g = None if grads is None else grads[i]
+        if g is not None and (g.shape != w.shape or not g.is_contiguous()):
+            raise ValueError(f"tensor {i}: gradient must be contiguous and shaped like the parameter")
+        arr[i].w = w.data_ptr()
+        arr[i].g = 0 if g is None else g.data_ptr()
+        arr[i].n = int(w.numel())
+        arr[i].w_dtype = _dtype_code(w.dtype)
+        arr[i].g_dtype = _dtype_code(g.dtype if g is not None else g_dtype)
+    return arr
+
+
+def mona_adamw_state_size(vecs, count: int) -> int:
+    out = C.c_size_t(0)
+    _check(load_library().mona_adamw_state_size(vecs, count, C.byref(out)))
+    return out.value
+
+
+def mona_adamw_step(state: int, vecs, count: int, hp: mona_adamw_hparams, stream: int) -> None:
+    _check(load_library().mona_adamw_step(state, vecs, count, C.byref(hp), stream))
+
+
+class AdamWOptimizer:
+    """Owns the arena and the state handle for a fixed list of non-matrix parameters."""
+
+    def __init__(self, params: Sequence[torch.Tensor], g_dtype: torch.dtype = torch.float32):
+        if not params:
+            raise ValueError("need at least one tensor")
+        self.lib = load_library()
+        self.device = params[0].device
+        if self.device.type != "cuda":
+            raise RuntimeError("AdamWOptimizer needs parameters on a GPU (no CPU path exists)")
+        self.params = list(params)
+        self.count = len(self.params)
+        self.g_dtype = g_dtype
+        shapes_only = make_vectors(self.params, None, g_dtype)
+        self.arena_bytes = mona_adamw_state_size(shapes_only, self.count)
+        self.arena = torch.empty(self.arena_bytes, dtype=torch.uint8, device=self.device)
+        handle = C.c_void_p(0)
+        _check(self.lib.mona_adamw_init_state(shapes_only, self.count, self.arena.data_ptr(), self.arena_bytes,
+                                              self._stream(), C.byref(handle)))
+        self.state = handle.value
+
+    def _stream(self) -> int:
+        with torch.cuda.device(self.device):
+            return torch.cuda.current_stream(self.device).cuda_stream
+
+    def __del__(self):
+        st = getattr(self, "state", None)
+        if st:
+            self.lib.mona_adamw_free_state(st)
+            self.state = None
+
+    def step(self, grads: Sequence[torch.Tensor], hp) -> None:
+        """hp: a mona_adamw_hparams, or any object with lr, beta1, beta2, eps, weight_decay."""
+        if not isinstance(hp, mona_adamw_hparams):
+            hp = mona_adamw_hparams(hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay)
+        vecs = make_vectors(self.params, grads)
+        mona_adamw_step(self.state, vecs, self.count, hp, self._stream())
+
+    def view(self, i: int, kind: int) -> torch.Tensor:
+        ptr, n = C.c_void_p(0), C.c_int64(0)
+        _check(self.lib.mona_adamw_state_view(self.state, i, kind, C.byref(ptr), C.byref(n)))
+        off = ptr.value - self.arena.data_ptr()
+        return self.arena[off: off + n.value * 4].view(torch.float32).view(self.params[i].shape)
+
+    def exp_avg(self, i): return self.view(i, MONA_ADAMW_VIEW_M)
+    def exp_avg_sq(self, i): return self.view(i, MONA_ADAMW_VIEW_V)
+
+    def step_count(self) -> int:
+        t = C.c_int64(0)
+        _check(self.lib.mona_adamw_state_step_count(self.state, C.byref(t)))
+        return t.value
+
+    def export_state(self) -> torch.Tensor:
+        n = C.c_size_t(0)
+        _check(self.lib.mona_adamw_state_export_size(self.state, C.byref(n)))
+        buf = torch.empty(n.value, dtype=torch.uint8, device=self.device)
+        _check(self.lib.mona_adamw_state_export(self.state, buf.data_ptr(), n.value, self._stream()))
+        return buf
+
+    def import_state(self, buf: torch.Tensor, step_count: int) -> None:
+        _check(self.lib.mona_adamw_state_import(self.state, buf.data_ptr(), buf.numel(), step_count, self._stream()))

@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libmona.so")
-SOURCES = ("mona_api.hip", "state_update.hip", "ns_gemm.hip")
+SOURCES = ("mona_api.hip", "state_update.hip", "ns_gemm.hip", "adamw.hip")
 ARCH = "gfx950"
 
 

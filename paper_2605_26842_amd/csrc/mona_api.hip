@@ -18,17 +18,26 @@
 using namespace mona;
 
 namespace {
-
 thread_local std::string g_err;
+}
 
-int fail(int code, const char* fmt, ...) {
+namespace mona {
+int api_fail(int code, const char* fmt, va_list ap) {
   char buf[512];
-  va_list ap;
-  va_start(ap, fmt);
   vsnprintf(buf, sizeof buf, fmt, ap);
-  va_end(ap);
   g_err = buf;
   return code;
+}
+}  // namespace mona
+
+namespace {
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  const int rc = api_fail(code, fmt, ap);
+  va_end(ap);
+  return rc;
 }
 
 #define HIP_TRY(expr)                                                                       \

@@ -2,6 +2,7 @@
 // Nothing here is part of the public ABI (see include/mona.h).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <stdarg.h>
 #include <stdint.h>
 
 namespace mona {
@@ -83,6 +84,9 @@ struct GemmArgs {
   float w_keep;             // 1 - eta * lambda
   float o_scale;            // eta * gamma
 };
+
+// records the text mona_last_error() returns (thread-local) and hands `code` back
+int api_fail(int code, const char* fmt, va_list ap);
 
 // kernels (defined in the .hip files)
 hipError_t launch_state_update(const MatStatic* stat, const MatDynamic* dyn, const BlockWork* work,

@@ -117,3 +117,36 @@ def test_binding_refuses_cpu_tensors_and_bad_layouts():
         B.make_matrices([torch.zeros(4, 6, dtype=torch.float16)])
     with pytest.raises(FileNotFoundError):
         B.load_library("/nonexistent/libmona.so")
+
+
+def vecs(*n, w=B.MONA_BF16, g=B.MONA_F32):
+    arr = (B.mona_vector * len(n))()
+    for i, k in enumerate(n):
+        arr[i].n, arr[i].w_dtype, arr[i].g_dtype = k, w, g
+    return arr
+
+
+def test_adamw_host_side_checks():
+    lib = B.load_library()
+    # two fp32 moments per element, each array padded to 256 bytes, plus small tables
+    one = B.mona_adamw_state_size(vecs(4096), 1)
+    assert 2 * 4096 * 4 <= one < 2 * 4096 * 4 + 4096
+    two = B.mona_adamw_state_size(vecs(4096, 5), 2)
+    assert two - one >= 2 * 256 and two - one < 4096
+    out = C.c_size_t(0)
+    rc, msg = rc_of(lib.mona_adamw_state_size, None, 1, C.byref(out))
+    assert rc == B.MONA_EINVAL and "NULL" in msg
+    rc, msg = rc_of(lib.mona_adamw_state_size, vecs(0), 1, C.byref(out))
+    assert rc == B.MONA_EINVAL and ">= 1" in msg
+    rc, _ = rc_of(lib.mona_adamw_state_size, vecs(8, w=3), 1, C.byref(out))
+    assert rc == B.MONA_EINVAL
+    handle = C.c_void_p(0)
+    rc, msg = rc_of(lib.mona_adamw_init_state, vecs(8), 1, None, 1 << 20, None, C.byref(handle))
+    assert rc == B.MONA_EINVAL and "arena" in msg
+    rc, msg = rc_of(lib.mona_adamw_init_state, vecs(1 << 20), 1, 0x10000, 1024, None, C.byref(handle))
+    assert rc == B.MONA_ENOMEM and "too small" in msg
+    hp = B.mona_adamw_hparams(1e-3, 0.9, 0.95, 1e-8, 0.1)
+    assert lib.mona_adamw_step(None, vecs(8), 1, C.byref(hp), None) == B.MONA_EINVAL
+    assert lib.mona_adamw_free_state(None) == B.MONA_OK
+    with pytest.raises(RuntimeError):
+        B.AdamWOptimizer([torch.zeros(8)])
