@@ -83,6 +83,64 @@ def cpu_baseline(workload, hp, budget_s: float = 30.0):
     }
 
 
+def bench_adamw(args) -> int:
+    """The AdamW step of the non-matrix parameters (its own JSON line; not part of the headline metric)."""
+    import numpy as np
+    import torch
+
+    from paper_2605_26842_amd import binding as B
+    from paper_2605_26842_amd import workloads as wl
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    name = args.adamw
+    shapes = wl.VECTOR_WORKLOADS[name]
+    params, ring = wl.draw_vector_inputs(shapes, 1, torch.bfloat16, torch.float32, dev, steps=2)
+    opt = B.AdamWOptimizer(params)
+    hp = B.mona_adamw_hparams(1e-3, 0.9, 0.95, 1e-8, 0.1)
+    n_elem = sum(int(np.prod(s)) for s in shapes)
+    nbytes = n_elem * (4 + 4 + 4 + 2 + 4 + 4 + 2)     # read g, m, v, w; write m, v, w
+    k = 0
+    for _ in range(args.warmup):
+        opt.step(ring[k % 2], hp); k += 1
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()       # the step is enqueued on torch's current stream, the one these events see
+    for _ in range(args.steps):
+        opt.step(ring[k % 2], hp); k += 1
+    e1.record()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_ev = e0.elapsed_time(e1) / args.steps
+    out = {
+        "metric": "AdamW steps/s (non-matrix parameters)", "value": 1e3 / ms, "unit": "steps/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": name, "tensors": len(shapes), "elements": n_elem, "param_dtype": "bfloat16",
+                   "grad_dtype": "f32"},
+        "roofline": {"kernel": "adamw_kernel<float, bf16>", "bound": "hbm", "achieved": nbytes / (ms_ev * 1e-3) / 1e9,
+                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": nbytes / (ms_ev * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                     "traffic": None, "bytes_per_step": nbytes, "ms_per_step": ms_ev},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import adamw_oracle as ao
+        n = 1 << 24
+        w = np.random.default_rng(0).standard_normal(n)
+        g = np.random.default_rng(1).standard_normal(n) * 1e-3
+        o = ao.AdamWOracle((n,))
+        t0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t0 < 10.0:
+            w = o.step(w, g, ao.AdamWHParams())
+            reps += 1
+        dt = (time.perf_counter() - t0) / reps
+        out["cpu_baseline"] = {"value": 1.0 / (dt * n_elem / n), "unit": "steps/s", "cores": 1, "kind": "oracle",
+                               "sample": f"float64 oracle step on {n} elements, {reps} repetitions, scaled by element count"}
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -103,6 +161,9 @@ def main() -> int:
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB elementwise copy (negation; a reference kernel of known traffic for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--adamw", default=None, metavar="VECTOR_WORKLOAD",
+                    help="instead of the MONA step, time the AdamW step of a set of non-matrix parameters "
+                         "(embeddings_h4096_v128k or small_vectors) and print its own JSON line")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -118,6 +179,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
+    if args.adamw:
+        return bench_adamw(args)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     workload = wl.WORKLOADS[args.workload]

@@ -243,3 +243,21 @@ def make_inputs(workload: Workload, workload_index: int = 0,
                for i, s in enumerate(shapes)]
     grads = [[st.next().to(g_dtype) for st in streams] for _ in range(steps)]
     return weights, grads
+
+
+# Non-matrix parameters of a model of the benchmark's size (Sec. 4.1: embeddings, biases and norm
+# gains are stepped by AdamW): an input embedding and an output head of 131072 x 4096 and the norm
+# gains of 24 layers.  bf16 parameters, fp32 gradients.
+VECTOR_WORKLOADS = {
+    "embeddings_h4096_v128k": tuple([(131072, 4096)] * 2 + [(4096,)] * 49),
+    "small_vectors": tuple([(4096,)] * 49 + [(1000,), (3,)]),
+}
+
+
+def draw_vector_inputs(shapes, seed: int, w_dtype: torch.dtype, g_dtype: torch.dtype, device, steps: int = 1):
+    """Seeded parameters N(0, 0.02^2) and `steps` gradient sets N(0, sigma^2) for tensors of any shape."""
+    gen = torch.Generator(device=device).manual_seed(BASE_SEED + 7919 * seed)
+    params = [(torch.randn(s, generator=gen, device=device) * WEIGHT_STD).to(w_dtype) for s in shapes]
+    grads = [[(torch.randn(s, generator=gen, device=device) * GRAD_SIGMA).to(g_dtype) for s in shapes]
+             for _ in range(steps)]
+    return params, grads
