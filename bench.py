@@ -161,6 +161,11 @@ def main() -> int:
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB elementwise copy (negation; a reference kernel of known traffic for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--streams", type=int, default=0,
+                    help="streams the shape groups' launch chains are spread over (0 = library default, 1 = one)")
+    ap.add_argument("--graph", action="store_true",
+                    help="record one step into a HIP graph and time replays of it (for launch-bound small "
+                         "workloads; uses one static gradient set)")
     ap.add_argument("--adamw", default=None, metavar="VECTOR_WORKLOAD",
                     help="instead of the MONA step, time the AdamW step of a set of non-matrix parameters "
                          "(embeddings_h4096_v128k or small_vectors) and print its own JSON line")
@@ -194,7 +199,7 @@ def main() -> int:
     weights = [wl.draw_weight(s, wl.matrix_seed(widx, i), workload.w_dtype, dev) for i, s in enumerate(shapes)]
     ring = []
     streams = None
-    for r in range(max(1, args.grad_ring)):
+    for r in range(1 if args.graph else max(1, args.grad_ring)):
         if streams is None:
             # one generator state per shape class keeps the host loop short; each matrix still
             # gets its own draw
@@ -203,7 +208,7 @@ def main() -> int:
     del streams
     accel_form = B.MONA_ACCEL_ONE_BUFFER if args.accel_form == "one-buffer" else B.MONA_ACCEL_TWO_BUFFER
     opt = B.MonaOptimizer(weights, ns_precision=args.ns_precision, state_dtype=state_dtype, g_dtype=g_dtype,
-                          accel_form=accel_form)
+                          accel_form=accel_form, max_streams=args.streams)
     hpc = B.make_hparams(hp)
     plan = opt.plan_info(hp.ns_steps)
     torch.cuda.synchronize()
@@ -221,6 +226,20 @@ def main() -> int:
         k += 1
     torch.cuda.synchronize()
 
+    graph = None
+    if args.graph:
+        opt.step(ring[0], hpc)      # the pointer table now names ring[0]: the capture holds launches only
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            opt.step(ring[0], hpc)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
     # timed region: exactly --steps steps; phase times come from HIP events that mona_step
     # records on the stream it launches on
     opt.set_profiling(1)
@@ -234,6 +253,9 @@ def main() -> int:
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    eager_ms = ms_per_step
+    if graph is not None:
+        ms_per_step = graph_ms      # the phase split below still comes from eager, profiled steps
     # events of the last timed step (the library keeps one set); then a few more profiled steps
     # outside the timed region to average the phase split
     times = opt.last_step_times()
@@ -299,6 +321,7 @@ def main() -> int:
             "param_dtype": str(workload.w_dtype).replace("torch.", ""), "grad_dtype": args.g_dtype,
             "state_dtype": args.state_dtype, "accel_form": args.accel_form, "ns_steps": hp.ns_steps, "ns_precision": args.ns_precision,
             "grad_ring": len(ring), "optimizer": "muon" if args.muon_only else "mona",
+            "launch": "hip graph replay" if graph is not None else "eager", "streams": args.streams,
         },
         "roofline": {
             "kernel": "ns_gemm (grouped Newton-Schulz products, %d launches/step)" % plan["ns_launches"],
@@ -321,6 +344,8 @@ def main() -> int:
         "ns_tflops_dense_equivalent": flops_dense / (ns_ms * 1e-3) / 1e12 if ns_ms > 0 else 0.0,
         "ns_tflops_issued": plan["ns_flops_issued"] / (ns_ms * 1e-3) / 1e12 if ns_ms > 0 else 0.0,
     }
+    if graph is not None:
+        out["eager_ms_per_step"] = eager_ms
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(workload, hp)
     print(json.dumps(out), flush=True)

@@ -101,7 +101,11 @@ typedef struct mona_options {
                            Sec. 6.3, reached without borrowing the caller's gradient slot -- and the
                            elementwise pass moves 22 instead of 30 bytes per element.  beta_a must
                            then stay the same from step to step (MONA_EINVAL otherwise)            */
-  int32_t reserved[5];  /* must be 0 */
+  int32_t max_streams;  /* matrices of different shapes are orthogonalised independently; their launch
+                           chains run on up to this many streams (the caller's plus side streams the
+                           state owns, forked after the elementwise pass and joined before mona_step
+                           returns, all at default priority).  0 = default (4), 1 = caller's stream only */
+  int32_t reserved[4];  /* must be 0 */
 } mona_options;
 
 #define MONA_ACCEL_TWO_BUFFER 0
@@ -130,7 +134,14 @@ int mona_init_state(const mona_matrix* mats, int32_t count, const mona_options* 
  * and returns without waiting.  `mats` must list the same shapes and dtypes, in the same
  * order, as at init (else MONA_ESHAPE); w and g pointers may differ from step to step.
  * Successive steps on one state must be issued on the same stream or be ordered by the
- * caller. */
+ * caller.
+ * Graph capture: with profiling off and the same w / g pointers as in the previous call
+ * (so that no pointer table is uploaded) the call enqueues only kernel launches and the
+ * event record / wait pairs that fork and join its side streams -- no memset, no copy --
+ * and may be recorded into a HIP graph on a capturing stream.
+ * The hyper-parameters are baked into the recorded launches, and the host-side step
+ * counter counts calls, not replays (it only matters for MONA_FLAG_FIRST_DIFF_ZERO at
+ * the first step). */
 int mona_step(mona_state* st, const mona_matrix* mats, int32_t count,
               const mona_hparams* hp, void* stream);
 
@@ -243,7 +254,9 @@ int mona_adamw_state_size(const mona_vector* vecs, int32_t count, size_t* bytes_
 int mona_adamw_init_state(const mona_vector* vecs, int32_t count, void* arena, size_t arena_bytes,
                           void* stream, mona_adamw_state** out);
 /* One AdamW step for every tensor, enqueued on `stream`, no wait.  Sizes and dtypes must
- * match init (MONA_ESHAPE otherwise); w and g pointers may change from step to step. */
+ * match init (MONA_ESHAPE otherwise); w and g pointers may change from step to step.
+ * Not for graph replay: the bias corrections 1 / (1 - beta^t) are computed on the host
+ * for this call's t and passed as launch arguments. */
 int mona_adamw_step(mona_adamw_state* st, const mona_vector* vecs, int32_t count,
                     const mona_adamw_hparams* hp, void* stream);
 int mona_adamw_free_state(mona_adamw_state* st);

@@ -59,7 +59,7 @@ class mona_hparams(C.Structure):
 
 class mona_options(C.Structure):
     _fields_ = [("ns_precision", C.c_int32), ("state_dtype", C.c_int32), ("accel_form", C.c_int32),
-                ("reserved", C.c_int32 * 5)]
+                ("max_streams", C.c_int32), ("reserved", C.c_int32 * 4)]
 
 
 class mona_view(C.Structure):
@@ -201,7 +201,7 @@ class MonaOptimizer:
 
     def __init__(self, weights: Sequence[torch.Tensor], ns_precision: int = 0,
                  state_dtype: torch.dtype = torch.float32, g_dtype: torch.dtype = torch.float32,
-                 accel_form: int = MONA_ACCEL_TWO_BUFFER):
+                 accel_form: int = MONA_ACCEL_TWO_BUFFER, max_streams: int = 0):
         if not weights:
             raise ValueError("need at least one matrix")
         self.lib = load_library()
@@ -211,7 +211,7 @@ class MonaOptimizer:
         self.weights = list(weights)
         self.count = len(self.weights)
         self.g_dtype = g_dtype
-        self.opts = mona_options(ns_precision, _dtype_code(state_dtype), accel_form, (C.c_int32 * 5)())
+        self.opts = mona_options(ns_precision, _dtype_code(state_dtype), accel_form, max_streams, (C.c_int32 * 4)())
         self.accel_form = accel_form
         self.ns_precision = ns_precision
         self.state_dtype = state_dtype

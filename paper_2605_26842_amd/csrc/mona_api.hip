@@ -112,6 +112,7 @@ int check_opts(const mona_options* o, mona_options* out) {
     return fail(MONA_EINVAL, "state_dtype must be MONA_F32 or MONA_BF16");
   if (z.accel_form != MONA_ACCEL_TWO_BUFFER && z.accel_form != MONA_ACCEL_ONE_BUFFER)
     return fail(MONA_EINVAL, "accel_form must be MONA_ACCEL_TWO_BUFFER or MONA_ACCEL_ONE_BUFFER");
+  if (z.max_streams < 0 || z.max_streams > 8) return fail(MONA_EINVAL, "max_streams must lie in [0, 8]");
   for (int r : z.reserved)
     if (r != 0) return fail(MONA_EINVAL, "reserved option fields must be 0");
   *out = z;
@@ -207,6 +208,8 @@ void build_layout(const mona_matrix* mats, int count, const mona_options& opt, L
 }
 
 constexpr int kRing = 4;
+constexpr int kDefaultLanes = 4;   // streams the shape groups of one step are spread over
+constexpr long long kBigLaunchTiles = 512;   // launches of at least this many tiles fill 256 CUs twice over
 
 struct LaunchRecord {
   int kind, group, iter, tile;
@@ -223,6 +226,13 @@ struct mona_state {
   char* arena = nullptr;
   int64_t k = 0;
   float last_beta_a = -1.0f;       // one-buffer form: beta_a of the previous step (< 0: none yet)
+  // Shape groups are independent of each other, so their Newton-Schulz chains run on separate
+  // streams: lane 0 is the caller's stream, lanes 1.. are side streams forked from it after the
+  // elementwise pass and joined back before mona_step returns.
+  std::vector<hipStream_t> side;       // lanes 1..
+  std::vector<hipEvent_t> side_done;   // one per side stream
+  hipEvent_t fork_ev = nullptr;
+  std::vector<int> lane_of_group;      // group index -> lane
   // pinned ring for the per-step pointer table
   MatDynamic* ring[kRing] = {nullptr, nullptr, nullptr, nullptr};
   hipEvent_t ring_ev[kRing];
@@ -261,6 +271,13 @@ TileShape pick_tile(const Group& g, int kind, int count) {
   }
   if (tiles < 192) return {128, 128};       // too few large tiles to fill 256 CUs
   return {256, 256};
+}
+
+// tiles one product launch of a group computes
+long long launch_tiles(const Group& g, int kind, TileShape tile, int count) {
+  if (kind == OP_APPLY) return (long long)(g.rows_pad / tile.bm) * (g.cols_pad / tile.bn) * count;
+  const long long t = g.p_pad / tile.bm;
+  return t * (t + 1) / 2 * count;
 }
 
 double gemm_flops(const GemmArgs& a) {
@@ -417,6 +434,9 @@ int mona_init_state(const mona_matrix* mats, int32_t count, const mona_options* 
       if (st->ring[i]) { (void)hipHostFree(st->ring[i]); (void)hipEventDestroy(st->ring_ev[i]); }
     }
     if (st->ev_valid) for (auto& e : st->ev) (void)hipEventDestroy(e);
+    for (hipStream_t q : st->side) (void)hipStreamDestroy(q);
+    for (hipEvent_t e : st->side_done) (void)hipEventDestroy(e);
+    if (st->fork_ev) (void)hipEventDestroy(st->fork_ev);
     delete st;
     return code;
   };
@@ -440,6 +460,44 @@ int mona_init_state(const mona_matrix* mats, int32_t count, const mona_options* 
   }
   for (auto& e : st->ev) INIT_TRY(hipEventCreate(&e));
   st->ev_valid = true;
+  {
+    // Lanes.  A group whose every launch covers the chip several times over gains nothing from company
+    // (two persistent kernels sharing the CUs only disturb each other's L2 reuse: measured slower), so
+    // such groups stay in a row on the caller's stream; the others, sorted by work, each go to the
+    // least loaded lane.
+    const int want = o.max_streams == 0 ? kDefaultLanes : o.max_streams;
+    const int lanes = std::max(1, std::min<int>(want, (int)L.groups.size()));
+    std::vector<std::pair<double, int>> order;
+    std::vector<double> load(lanes, 0.0);
+    st->lane_of_group.assign(L.groups.size(), 0);
+    for (size_t gi = 0; gi < L.groups.size(); ++gi) {
+      const Group& g = L.groups[gi];
+      const double p = std::min(g.rows_pad, g.cols_pad), q = std::max(g.rows_pad, g.cols_pad);
+      const double work = (3.0 * p * p * q + p * p * p) * (double)g.members.size();
+      long long fewest = -1;
+      for (int kind = OP_GRAM; kind <= OP_APPLY; ++kind) {
+        const long long t = launch_tiles(g, kind, pick_tile(g, kind, (int)g.members.size()), (int)g.members.size());
+        if (fewest < 0 || t < fewest) fewest = t;
+      }
+      if (fewest >= kBigLaunchTiles) load[0] += work;
+      else order.emplace_back(-work, (int)gi);
+    }
+    std::sort(order.begin(), order.end());
+    for (auto& pr : order) {
+      const int lane = (int)(std::min_element(load.begin(), load.end()) - load.begin());
+      st->lane_of_group[pr.second] = lane;
+      load[lane] += -pr.first;
+    }
+    INIT_TRY(hipEventCreateWithFlags(&st->fork_ev, hipEventDisableTiming));
+    for (int i = 1; i < lanes; ++i) {
+      hipStream_t side = nullptr;
+      INIT_TRY(hipStreamCreateWithFlags(&side, hipStreamNonBlocking));
+      st->side.push_back(side);
+      hipEvent_t done = nullptr;
+      INIT_TRY(hipEventCreateWithFlags(&done, hipEventDisableTiming));
+      st->side_done.push_back(done);
+    }
+  }
 
   // Alg. 1 initialisation: M_0 = A_0 = G_0 = 0; the padded working copies start (and stay) zero
   INIT_TRY(launch_fill_zero(st->arena + L.state_begin, L.state_bytes + L.work_bytes, s));
@@ -557,9 +615,17 @@ int mona_step(mona_state* st, const mona_matrix* mats, int32_t count, const mona
   const int T = hp->ns_steps;
   st->fused_update = T > 0;
   st->o_buf = (T == 0) ? 1 : (T & 1);
+  // per-launch timing serialises the launches on the caller's stream so that each interval is one kernel
+  const bool fork = !st->side.empty() && st->profiling < 2 && T > 0;
+  if (fork) {
+    HIP_TRY(hipEventRecord(st->fork_ev, s));
+    for (hipStream_t q : st->side) HIP_TRY(hipStreamWaitEvent(q, st->fork_ev, 0));
+  }
   for (size_t gi = 0; gi < L.groups.size(); ++gi) {
     const Group& g = L.groups[gi];
     const int cnt = (int)g.members.size();
+    const int lane = fork ? st->lane_of_group[gi] : 0;
+    hipStream_t gs = lane == 0 ? s : st->side[lane - 1];
     int src = 0;
     for (int t = 0; t < T; ++t) {
       for (int kind = OP_GRAM; kind <= OP_APPLY; ++kind) {
@@ -571,17 +637,23 @@ int mona_step(mona_state* st, const mona_matrix* mats, int32_t count, const mona
         const bool each = st->profiling > 1;
         if (each) {
           if (!get_event_pair(st, &rec.e0, &rec.e1)) return fail(MONA_EHIP, "hipEventCreate failed");
-          HIP_TRY(hipEventRecord(rec.e0, s));
+          HIP_TRY(hipEventRecord(rec.e0, gs));
         }
-        HIP_TRY(launch_ns_gemm(a, tile.bm, tp, tq, g.f32, s));
+        HIP_TRY(launch_ns_gemm(a, tile.bm, tp, tq, g.f32, gs));
         if (each) {
-          HIP_TRY(hipEventRecord(rec.e1, s));
+          HIP_TRY(hipEventRecord(rec.e1, gs));
           rec.kind = kind; rec.group = (int)gi; rec.iter = t; rec.tile = tile.bm * 1000 + tile.bn;
           rec.flops = gemm_flops(a);
           st->records.push_back(rec);
         }
       }
       src ^= 1;
+    }
+  }
+  if (fork) {
+    for (size_t i = 0; i < st->side.size(); ++i) {
+      HIP_TRY(hipEventRecord(st->side_done[i], st->side[i]));
+      HIP_TRY(hipStreamWaitEvent(s, st->side_done[i], 0));
     }
   }
   if (prof) HIP_TRY(hipEventRecord(st->ev[2], s));
@@ -606,6 +678,9 @@ int mona_free_state(mona_state* st) {
   }
   if (st->ev_valid) for (auto& e : st->ev) (void)hipEventDestroy(e);
   for (auto& pr : st->event_pool) { (void)hipEventDestroy(pr.first); (void)hipEventDestroy(pr.second); }
+  for (hipStream_t q : st->side) { (void)hipStreamSynchronize(q); (void)hipStreamDestroy(q); }
+  for (hipEvent_t e : st->side_done) (void)hipEventDestroy(e);
+  if (st->fork_ev) (void)hipEventDestroy(st->fork_ev);
   delete st;
   return MONA_OK;
 }

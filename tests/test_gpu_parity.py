@@ -297,6 +297,42 @@ def test_checkpoint_round_trip_and_determinism():
         assert torch.equal(opt_b.momentum(i), torch.from_numpy(hist_full[-1][i].M).float().cuda())
 
 
+def test_step_captured_in_a_hip_graph_replays_like_eager_steps():
+    """mona_step records kernel launches only (no memset, no event, no table upload when the pointers are
+    those of the previous call), so a caller may capture it; every replay must equal the eager step."""
+    say("[case] HIP graph capture")
+    w, weights, grads = inputs("ragged_mix", steps=6)
+    hp = wl.HParams()
+    dev = "cuda:0"
+    w_eager = [t.to(dev).contiguous() for t in weights]
+    opt_e = B.MonaOptimizer(w_eager)
+    w_graph = [t.to(dev).contiguous() for t in weights]
+    opt_g = B.MonaOptimizer(w_graph)
+    static = [g.to(dev).contiguous() for g in grads[0]]
+    # step 1 eagerly on both (uploads the graph optimizer's pointer table)
+    opt_e.step([g.to(dev) for g in grads[0]], hp)
+    opt_g.step(static, hp)
+    torch.cuda.synchronize()
+    # capture one step reading the static gradient buffers; capture only records, nothing runs
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        opt_g.step(static, hp)
+    torch.cuda.synchronize()
+    assert opt_g.step_count() == 2          # the host-side counter counts calls, not replays
+    for k in range(1, 6):
+        for dst, src in zip(static, grads[k]):
+            dst.copy_(src)                      # eager work between the replays
+        opt_e.step([g.to(dev) for g in grads[k]], hp)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i in range(len(weights)):
+            assert torch.equal(w_graph[i], w_eager[i]), f"replay {k}, matrix {i}: parameters differ"
+            assert torch.equal(opt_g.momentum(i), opt_e.momentum(i)), f"replay {k}, matrix {i}: M differs"
+            assert torch.equal(opt_g.accel(i), opt_e.accel(i)), f"replay {k}, matrix {i}: A differs"
+            assert torch.equal(opt_g.g_prev(i), opt_e.g_prev(i)), f"replay {k}, matrix {i}: G_prev differs"
+
+
 def test_step_rejects_changed_matrix_list():
     w = [torch.zeros(64, 64, device="cuda:0"), torch.zeros(64, 32, device="cuda:0")]
     opt = B.MonaOptimizer(w)
