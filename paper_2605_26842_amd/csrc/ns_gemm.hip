@@ -513,6 +513,195 @@ struct FineEpilogue {
   }
 };
 
+#define MONA_AS3_EPI __attribute__((address_space(3)))
+// Epilogue of the persistent kernel for accumulators held TRANSPOSED (the kernel feeds the Q fragment
+// as the first MFMA operand): lane l of a 32 x 32 block then holds row l % 32 of the output and, per
+// group of four registers, four CONSECUTIVE columns, so a whole block row (32 rows x 64 columns of this
+// wavefront) is staged with 8 ds_write_b128 instead of 32 ds_write_b32.  Four passes of 8 rows x 64
+// columns follow, each lane reading 8 consecutive floats back: one 16-byte chunk of E, of C and (fused
+// update) of W per lane and pass, exactly the global access pattern of FineEpilogue.
+// Staging area per wavefront: 32 rows of 256 bytes (no padding; the 16-byte chunk index is XORed with
+// row % 16, which spreads both the column-wise writes and the row-wise reads over all banks).
+// Mirrored (symmetric) tiles: each pass leaves its rounded bf16 row in the 256 bytes of the fp32 row it
+// has just consumed (at 32 (row % 4) bytes inside it), and ds_read_b64_tr_b16 then hands every lane 4
+// consecutive rows of one column: two of them make the 16-byte piece of the transposed tile.
+//
+// Global loads and stores: the load counter of this target counts both and stores retire out of order,
+// so once a store is in flight every wait for a load drains everything, stores included.  The E chunks
+// (and the parameter chunks of the fused update) of a whole batch of NPF passes are therefore requested
+// together, waited for ONCE (settle(), which also tells the compiler that these registers hold plain
+// values from then on), and the stores of the passes then stream without any wait.  HAS_E is a template
+// parameter for the same reason: a run-time test around the loads would make every later use look as if
+// it might still be pending.
+template <int MI, int NPF, int NPRE, bool UPD, bool HAS_E>
+struct BlockEpilogue {
+  static constexpr int NI = 2, WN = 64, CH = 8, PASSES = MI * 4;
+  static constexpr int kStageBytesPerWave = 32 * WN * 4;
+  static_assert(NPF == 8 || NPF == 16, "settle() is written for batches of 8 or 16 passes");
+
+  const GemmArgs& a;
+  int lane, row_w0, col_w0;
+  bool mirror, skip_w, w_pref;
+  float post;
+  const bf16_t* __restrict__ E;
+  bf16_t* __restrict__ C;
+  int wm_real, wn_real, w_is_bf16;
+  void* wptr;
+  u32x4 ev[HAS_E ? NPF : 1];
+  u32x4 wv[UPD ? NPF : 1];     // parameter chunks, only in the launch that carries the update
+
+  __device__ __forceinline__ BlockEpilogue(const GemmArgs& args) : a(args), lane(threadIdx.x & 63) {}
+
+  // one wait for everything requested so far; afterwards the batch registers are ordinary values
+  __device__ __forceinline__ void settle() {
+    if constexpr (HAS_E) {
+      asm volatile("s_waitcnt vmcnt(0)"
+                   : "+v"(ev[0]), "+v"(ev[1]), "+v"(ev[2]), "+v"(ev[3]), "+v"(ev[4]), "+v"(ev[5]), "+v"(ev[6]), "+v"(ev[7]));
+      if constexpr (NPF == 16)
+        asm volatile("" : "+v"(ev[8]), "+v"(ev[9]), "+v"(ev[10]), "+v"(ev[11]), "+v"(ev[12]), "+v"(ev[13]),
+                     "+v"(ev[14]), "+v"(ev[15]));
+    }
+    if constexpr (UPD) {
+      static_assert(!UPD || NPF == 8, "the fused update fetches 8 passes at a time");
+      asm volatile("s_waitcnt vmcnt(0)"
+                   : "+v"(wv[0]), "+v"(wv[1]), "+v"(wv[2]), "+v"(wv[3]), "+v"(wv[4]), "+v"(wv[5]), "+v"(wv[6]), "+v"(wv[7]));
+    }
+  }
+
+  __device__ __forceinline__ void begin(int tmat, int row0, int col0, bool mir) {
+    row_w0 = row0; col_w0 = col0; mirror = mir;
+    const int mi = a.members ? a.members[tmat] : tmat;
+    post = 1.0f;
+    if (a.post == POST_INV) post = a.scales[mi].inv;
+    else if (a.post == POST_INV2) post = a.scales[mi].inv2;
+    E = HAS_E ? static_cast<const bf16_t*>(a.E) + (size_t)tmat * a.strideE : nullptr;
+    C = static_cast<bf16_t*>(a.C) + (size_t)tmat * a.strideC;
+    wm_real = wn_real = w_is_bf16 = 0;
+    skip_w = true;
+    wptr = nullptr;
+    if constexpr (UPD) {
+      const MatStatic& ms = a.stat[mi];
+      wm_real = ms.m; wn_real = ms.n; w_is_bf16 = ms.w_dtype;
+      wptr = a.dyn[mi].w;
+      skip_w = (a.scales[mi].status & 2u) != 0;
+    }
+    w_pref = UPD && !skip_w && w_is_bf16 && (wn_real % CH) == 0;
+  }
+
+  // first row of pass p inside the wavefront tile: block row p / 4, rows 8 (p % 4) .. + 7
+  static __device__ __forceinline__ constexpr int pass_row(int p) { return (p >> 2) * 32 + (p & 3) * 8; }
+
+  template <int P>
+  __device__ __forceinline__ void prefetch() {
+    constexpr int slot = P % NPF;
+    const int grow = row_w0 + pass_row(P) + (lane >> 3), gcol = col_w0 + (lane & 7) * CH;
+    if constexpr (HAS_E) ev[slot] = *reinterpret_cast<const u32x4*>(E + (size_t)grow * a.lde + gcol);
+    if constexpr (UPD) {
+      if (w_pref && grow < wm_real && gcol + CH <= wn_real)
+        wv[slot] = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(wptr) + (size_t)grow * wn_real + gcol);
+    }
+  }
+  __device__ __forceinline__ void prefetch_first() {
+    static_for<NPRE>([&](auto p) { prefetch<p>(); });
+  }
+
+  // acc[i][j]: block (i, j) of the wavefront tile, transposed operand roles (see above).
+  // stage: kStageBytesPerWave bytes of LDS private to this wavefront, 256-byte aligned.
+  __device__ __forceinline__ void run(f32x16 (&acc)[MI][NI], char* stage) {
+    static_assert(NPRE <= NPF && PASSES % NPF == 0, "passes are fetched in batches of NPF");
+    static_for<NPF - NPRE>([&](auto p) { prefetch<NPRE + p>(); });
+    const int srow = lane & 31, shalf = lane >> 5;       // staging writes: row and 4-column half
+    const int prow = lane >> 3, q = lane & 7;            // passes: row inside the pass and 8-column chunk
+    const uint32_t stage_addr = (uint32_t)(uintptr_t)(MONA_AS3_EPI const char*)stage;
+    static_for<MI>([&](auto i) {
+      wave_sync();         // previous block row fully consumed
+      static_for<NI>([&](auto j) {
+        static_for<4>([&](auto vg) {
+          const int c = j * 8 + 2 * vg + shalf;
+          f32x4 v = {acc[i][j][vg * 4 + 0], acc[i][j][vg * 4 + 1], acc[i][j][vg * 4 + 2], acc[i][j][vg * 4 + 3]};
+          *reinterpret_cast<f32x4*>(stage + srow * 256 + ((c ^ (srow & 15)) << 4)) = v;
+        });
+      });
+      wave_sync();
+      // the batch this block row starts: request it (the first one was requested above) and wait once,
+      // after the staging writes so that they overlap the latency
+      if constexpr ((i * 4) % NPF == 0) {
+        if constexpr (i > 0) static_for<NPF>([&](auto k) { prefetch<i * 4 + k>(); });
+        settle();
+      }
+      static_for<4>([&](auto pp) {
+        constexpr int p = i * 4 + pp;
+        constexpr int slot = p % NPF;
+        const int r = pp * 8 + prow;
+        const int grow = row_w0 + pass_row(p) + prow, gcol = col_w0 + q * CH;
+        float val[CH];
+        {
+          const f32x4 t0 = *reinterpret_cast<const f32x4*>(stage + r * 256 + (((2 * q) ^ (r & 15)) << 4));
+          const f32x4 t1 = *reinterpret_cast<const f32x4*>(stage + r * 256 + (((2 * q + 1) ^ (r & 15)) << 4));
+          val[0] = t0.x; val[1] = t0.y; val[2] = t0.z; val[3] = t0.w;
+          val[4] = t1.x; val[5] = t1.y; val[6] = t1.z; val[7] = t1.w;
+        }
+        if constexpr (HAS_E) {
+          const bf16x8 e8 = __builtin_bit_cast(bf16x8, ev[slot]);
+#pragma unroll
+          for (int e = 0; e < CH; ++e) val[e] = post * (a.alpha * val[e] + a.beta * (float)e8[e]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < CH; ++e) val[e] = post * (a.alpha * val[e]);
+        }
+        bf16x8 ov;
+#pragma unroll
+        for (int e = 0; e < CH; ++e) ov[e] = (bf16_t)val[e];
+        if (!UPD || a.store_out) *reinterpret_cast<bf16x8*>(C + (size_t)grow * a.ldc + gcol) = ov;
+        // the rounded row, for the transposed store below: inside the fp32 row just read
+        if (mirror) *reinterpret_cast<bf16x8*>(stage + r * 256 + (r & 3) * 32 + q * 16) = ov;
+        if (UPD && !skip_w && grow < wm_real) {
+          // W <- (1 - eta lambda) W - eta gamma O, O as stored in the working precision
+          const size_t wi = (size_t)grow * wn_real + gcol;
+          if (w_pref && gcol + CH <= wn_real) {
+            bf16x8 w_in = __builtin_bit_cast(bf16x8, wv[UPD ? slot : 0]);
+#pragma unroll
+            for (int e = 0; e < CH; ++e) w_in[e] = (bf16_t)(a.w_keep * (float)w_in[e] - a.o_scale * (float)ov[e]);
+            *reinterpret_cast<bf16x8*>(static_cast<bf16_t*>(wptr) + wi) = w_in;
+          } else {
+#pragma unroll
+            for (int e = 0; e < CH; ++e) {
+              if (gcol + e < wn_real) {
+                if (w_is_bf16) {
+                  bf16_t* w = static_cast<bf16_t*>(wptr) + wi + e;
+                  *w = (bf16_t)(a.w_keep * (float)*w - a.o_scale * (float)ov[e]);
+                } else {
+                  float* w = static_cast<float*>(wptr) + wi + e;
+                  *w = a.w_keep * *w - a.o_scale * (float)ov[e];
+                }
+              }
+            }
+          }
+        }
+      });
+      if (mirror) {
+        // 16 lanes fetch a 4 (rows) x 16 (columns) block of the bf16 rows: lane j of the group points at
+        // row j / 4, columns 4 (j % 4) .. + 3 and receives the 4 rows of column j.  Group g of the
+        // wavefront takes columns 16 g .. 16 g + 15; two reads (rows r0 .. r0 + 3 and r0 + 4 .. r0 + 7,
+        // 4 x 256 bytes further on) give 8 consecutive rows of the lane's column.
+        wave_sync();
+        const int j16 = lane & 15, g = lane >> 4;
+        static_for<4>([&](auto h) {
+          const int rr = h * 8 + (j16 >> 2);
+          const uint32_t addr = stage_addr + rr * 256 + (rr & 3) * 32 + (16 * g + 4 * (j16 & 3)) * 2;
+          u32x2 lo, hi;
+          asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(addr));
+          asm volatile("ds_read_b64_tr_b16 %0, %1 offset:1024" : "=v"(hi) : "v"(addr));
+          asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(lo), "+v"(hi));
+          const u32x4 tv = {lo.x, lo.y, hi.x, hi.y};
+          const int n = 16 * g + j16;
+          *reinterpret_cast<u32x4*>(C + (size_t)(col_w0 + n) * a.ldc + row_w0 + i * 32 + h * 8) = tv;
+        });
+      }
+    });
+  }
+};
+
 // ---- bf16 kernel -----------------------------------------------------------------------------
 template <int BM, int BN, bool TP, bool TQ>
 __global__ __launch_bounds__(kThreads) void ns_gemm_bf16_kernel(const GemmArgs a) {
@@ -688,7 +877,7 @@ __device__ __forceinline__ void lds_read_t(FragT& f, uint32_t addr) {
 #define MONA_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
 #endif
 
-template <int BM, int BN, int WGM, int WGN, int STAGES, int MIN_BLOCKS, bool TP, bool TQ, bool UPD>
+template <int BM, int BN, int WGM, int WGN, int STAGES, int MIN_BLOCKS, bool TP, bool TQ, bool UPD, bool HAS_E>
 __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_kernel(const GemmArgs a) {
   constexpr int BK = 32;
   constexpr int NW = WGM * WGN;
@@ -701,7 +890,14 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
   static_assert(NLP * 64 * NW == P_U && NLQ * 64 * NW == Q_U, "tiles must split evenly over the wavefronts");
   constexpr int kStageFloats = NW * 32 * (WN + 4);
   static_assert(kStageFloats * 4 <= STAGES * STAGE_U * 16, "epilogue staging must fit in the operand ring");
-  __shared__ __attribute__((aligned(16))) u32x4 lds[STAGES * STAGE_U];
+#ifdef MONA_FINE_EPILOGUE
+  constexpr int LDS_U = STAGES * STAGE_U;
+#else
+  // the ring, and behind it what the epilogue's staging needs beyond the last stage
+  constexpr int LDS_U = STAGES * STAGE_U + (NW * 8192 / 16 - STAGE_U);
+  static_assert(LDS_U * 16 <= 160 * 1024, "LDS of one CU");
+#endif
+  __shared__ __attribute__((aligned(256))) u32x4 lds[LDS_U];
 
   MONA_STAMP(0);
   const int lane = threadIdx.x & 63;
@@ -827,7 +1023,13 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
   auto multiply = [&](auto slot) {
     static_for<MI>([&](auto i) {
       static_for<NI>([&](auto j) {
+#ifdef MONA_FINE_EPILOGUE
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i].get(), fb[slot][j].get(), acc[i][j], 0, 0, 0);
+#else
+        // operand roles swapped: the block is accumulated transposed (lane = output row), which is the
+        // layout the epilogue stages with 16-byte LDS writes
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[slot][j].get(), fa[slot][i].get(), acc[i][j], 0, 0, 0);
+#endif
       });
     });
   };
@@ -858,11 +1060,20 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
   };
 
   static_assert(STAGES == 4, "the pipeline below is written for a ring of 4 stages");
+#ifdef MONA_FINE_EPILOGUE
   typedef FineEpilogue<MI, NI, /*batch*/ (UPD ? 4 : 8), /*early*/ 2, UPD> Epi;
   Epi epi(a);
   static_assert(NW * Epi::kStageFloatsPerWave * 4 <= STAGE_U * 16, "epilogue staging must fit in the last stage");
   // epilogue staging lives in stage 3, which the next tile's early loads (stages 0..2) leave alone
   float* const stage_f = reinterpret_cast<float*>(lds + 3 * STAGE_U) + wave * Epi::kStageFloatsPerWave;
+#else
+  typedef BlockEpilogue<MI, /*batch*/ (UPD ? 8 : 16), /*early*/ 2, UPD, HAS_E> Epi;
+  Epi epi(a);
+  static_assert(NI == Epi::NI && (3 * STAGE_U * 16 + NW * Epi::kStageBytesPerWave) <= LDS_U * 16,
+                "epilogue staging: stage 3 and the LDS behind the ring");
+  // epilogue staging starts at stage 3, which the next tile's early loads (stages 0..2) leave alone
+  char* const stage_f = reinterpret_cast<char*>(lds + 3 * STAGE_U) + wave * Epi::kStageBytesPerWave;
+#endif
 
   TileId t = tile_at(0);
   if (!t.valid) return;
@@ -1088,17 +1299,16 @@ hipError_t launch_ns_gemm(const GemmArgs& a, int tile, bool transP, bool transQ,
       return n / kXcds * kXcds;
     }();
     const int pgrid = grid < num_cus ? grid : num_cus;
-#define MONA_LAUNCH_DMA(TP_, TQ_)                                                                              \
-  do {                                                                                                         \
-    if (a.epilogue == EPI_UPDATE)                                                                              \
-      hipLaunchKernelGGL((ns_gemm_bf16_dma_kernel<256, 256, 2, 4, 4, 1, TP_, TQ_, true>), dim3(pgrid), dim3(512), 0, s, a);  \
-    else                                                                                                       \
-      hipLaunchKernelGGL((ns_gemm_bf16_dma_kernel<256, 256, 2, 4, 4, 1, TP_, TQ_, false>), dim3(pgrid), dim3(512), 0, s, a); \
-  } while (0)
-    if (!transP && !transQ) MONA_LAUNCH_DMA(false, false);
-    else if (!transP && transQ) MONA_LAUNCH_DMA(false, true);
-    else if (transP && transQ && a.epilogue != EPI_UPDATE)     // Gram of a tall matrix: never carries the update
-      hipLaunchKernelGGL((ns_gemm_bf16_dma_kernel<256, 256, 2, 4, 4, 1, true, true, false>), dim3(pgrid), dim3(512), 0, s, a);
+#define MONA_LAUNCH_DMA(TP_, TQ_, UPD_, E_)                                                                        \
+  hipLaunchKernelGGL((ns_gemm_bf16_dma_kernel<256, 256, 2, 4, 4, 1, TP_, TQ_, UPD_, E_>), dim3(pgrid), dim3(512), 0, s, a)
+    const bool upd = a.epilogue == EPI_UPDATE, has_e = a.E != nullptr;
+    // the plan uses: Gram (no E; both operands plain or both K-major), poly and apply (with E; P plain)
+    if (!transP && !transQ && !upd && !has_e) MONA_LAUNCH_DMA(false, false, false, false);
+    else if (transP && transQ && !upd && !has_e) MONA_LAUNCH_DMA(true, true, false, false);
+    else if (!transP && !transQ && !upd && has_e) MONA_LAUNCH_DMA(false, false, false, true);
+    else if (!transP && transQ && !upd && has_e) MONA_LAUNCH_DMA(false, true, false, true);
+    else if (!transP && !transQ && upd && has_e) MONA_LAUNCH_DMA(false, false, true, true);
+    else if (!transP && transQ && upd && has_e) MONA_LAUNCH_DMA(false, true, true, true);
     else return hipErrorInvalidValue;
 #undef MONA_LAUNCH_DMA
     dma_debug_report(a, transP, transQ, pgrid, total);
