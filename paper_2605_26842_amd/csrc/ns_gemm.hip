@@ -514,6 +514,22 @@ struct FineEpilogue {
 };
 
 #define MONA_AS3_EPI __attribute__((address_space(3)))
+// Eight transposed LDS reads (4 rows x 16 columns of bf16 per group of 16 lanes and read), 1024 bytes =
+// 4 staged rows apart, then one wait.  A free function: an asm statement cannot name variables captured
+// by a lambda.  The destination registers are written when the data returns and stay untouched until
+// the wait, which is tied to them.
+__device__ __forceinline__ void tr_read_32_rows(u32x2 (&lo)[4], u32x2 (&hi)[4], uint32_t addr) {
+  asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo[0]) : "v"(addr));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:1024" : "=v"(hi[0]) : "v"(addr));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:2048" : "=v"(lo[1]) : "v"(addr));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:3072" : "=v"(hi[1]) : "v"(addr));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:4096" : "=v"(lo[2]) : "v"(addr));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:5120" : "=v"(hi[2]) : "v"(addr));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:6144" : "=v"(lo[3]) : "v"(addr));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:7168" : "=v"(hi[3]) : "v"(addr));
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(lo[0]), "+v"(hi[0]), "+v"(lo[1]), "+v"(hi[1]), "+v"(lo[2]), "+v"(hi[2]), "+v"(lo[3]), "+v"(hi[3]));
+}
 // Epilogue of the persistent kernel for accumulators held TRANSPOSED (the kernel feeds the Q fragment
 // as the first MFMA operand): lane l of a 32 x 32 block then holds row l % 32 of the output and, per
 // group of four registers, four CONSECUTIVE columns, so a whole block row (32 rows x 64 columns of this
@@ -629,6 +645,15 @@ struct BlockEpilogue {
         if constexpr (i > 0) static_for<NPF>([&](auto k) { prefetch<i * 4 + k>(); });
         settle();
       }
+      // all reads of the block row are issued before the first result is used: one LDS round trip per
+      // block row instead of one per pass (and every staged row is read before a pass overwrites part of
+      // it with its bf16 row)
+      f32x4 t[4][2];
+      static_for<4>([&](auto pp) {
+        const int r = pp * 8 + prow;
+        t[pp][0] = *reinterpret_cast<const f32x4*>(stage + r * 256 + (((2 * q) ^ (r & 15)) << 4));
+        t[pp][1] = *reinterpret_cast<const f32x4*>(stage + r * 256 + (((2 * q + 1) ^ (r & 15)) << 4));
+      });
       static_for<4>([&](auto pp) {
         constexpr int p = i * 4 + pp;
         constexpr int slot = p % NPF;
@@ -636,8 +661,7 @@ struct BlockEpilogue {
         const int grow = row_w0 + pass_row(p) + prow, gcol = col_w0 + q * CH;
         float val[CH];
         {
-          const f32x4 t0 = *reinterpret_cast<const f32x4*>(stage + r * 256 + (((2 * q) ^ (r & 15)) << 4));
-          const f32x4 t1 = *reinterpret_cast<const f32x4*>(stage + r * 256 + (((2 * q + 1) ^ (r & 15)) << 4));
+          const f32x4 t0 = t[pp][0], t1 = t[pp][1];
           val[0] = t0.x; val[1] = t0.y; val[2] = t0.z; val[3] = t0.w;
           val[4] = t1.x; val[5] = t1.y; val[6] = t1.z; val[7] = t1.w;
         }
@@ -686,15 +710,13 @@ struct BlockEpilogue {
         // 4 x 256 bytes further on) give 8 consecutive rows of the lane's column.
         wave_sync();
         const int j16 = lane & 15, g = lane >> 4;
+        const int rr = j16 >> 2;     // + 8 h; (rr + 8 h) % 4 == rr
+        const uint32_t addr = stage_addr + rr * 256 + rr * 32 + (16 * g + 4 * (j16 & 3)) * 2;
+        u32x2 lo[4], hi[4];
+        tr_read_32_rows(lo, hi, addr);
+        const int n = 16 * g + j16;
         static_for<4>([&](auto h) {
-          const int rr = h * 8 + (j16 >> 2);
-          const uint32_t addr = stage_addr + rr * 256 + (rr & 3) * 32 + (16 * g + 4 * (j16 & 3)) * 2;
-          u32x2 lo, hi;
-          asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(addr));
-          asm volatile("ds_read_b64_tr_b16 %0, %1 offset:1024" : "=v"(hi) : "v"(addr));
-          asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(lo), "+v"(hi));
-          const u32x4 tv = {lo.x, lo.y, hi.x, hi.y};
-          const int n = 16 * g + j16;
+          const u32x4 tv = {lo[h].x, lo[h].y, hi[h].x, hi[h].y};
           *reinterpret_cast<u32x4*>(C + (size_t)(col_w0 + n) * a.ldc + row_w0 + i * 32 + h * 8) = tv;
         });
       }
