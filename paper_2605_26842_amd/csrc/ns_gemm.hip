@@ -49,6 +49,8 @@ __device__ __forceinline__ void static_for(F&& f) {
 }
 
 // ---- tile decode ---------------------------------------------------------------------
+constexpr int kBandRows = 6;
+
 struct TileId {
   int mat, ti, tj;
   bool valid;
@@ -70,8 +72,16 @@ __device__ __forceinline__ TileId decode_logical(const GemmArgs& a, int logical,
     t.ti = ti;
     t.tj = ti * a.sym_ratio + r;
   } else {
-    t.ti = r / a.tiles_n;
-    t.tj = r - t.ti * a.tiles_n;
+    // Bands of up to kBandRows tile rows, walked column by column: the 32 workgroups of a die then hold
+    // a block of about 6 x 5 tiles at any time, which shares 11 operand panels in the die's L2 instead of
+    // the 18 of two full tile rows.
+    const int full = a.tiles_m / kBandRows;                 // complete bands
+    const int in_full = full * kBandRows * a.tiles_n;
+    int rows = kBandRows, first = 0;
+    if (r >= in_full) { r -= in_full; rows = a.tiles_m - full * kBandRows; first = full * kBandRows; }
+    else { const int b = r / (kBandRows * a.tiles_n); r -= b * kBandRows * a.tiles_n; first = b * kBandRows; }
+    t.tj = r / rows;
+    t.ti = first + (r - t.tj * rows);
   }
   return t;
 }
