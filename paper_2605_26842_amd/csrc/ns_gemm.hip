@@ -381,148 +381,6 @@ struct Epilogue {
   }
 };
 
-// The same epilogue for the persistent kernel below (bf16, 64-column wavefront tiles), in bands of
-// 8 rows: one 16-byte chunk per lane and band, E and parameter chunks fetched NPF bands ahead, and a
-// staging area of only 8 x 68 floats per wavefront, which leaves the rest of the LDS free for the
-// operand stages of the next tile that are being filled meanwhile.
-template <int MI, int NI, int NPF, int NPRE, bool UPD>
-struct FineEpilogue {
-  static constexpr int WN = 64, CH = 8, LDW = WN + 4, BANDS = MI * 4;
-  static constexpr int kStageFloatsPerWave = 8 * LDW;
-  static_assert(NI * 32 == WN, "wavefront tile is 64 columns wide");
-
-  const GemmArgs& a;
-  int lane, row_w0, col_w0;
-  bool mirror, update, skip_w, w_pref;
-  float post;
-  const bf16_t* __restrict__ E;
-  bf16_t* __restrict__ C;
-  int wm_real, wn_real, w_is_bf16;
-  void* wptr;
-  bf16x8 ev[NPF];
-  bf16x8 wv[UPD ? NPF : 1];    // parameter chunks, only in the launch that carries the update
-
-  __device__ __forceinline__ FineEpilogue(const GemmArgs& args) : a(args), lane(threadIdx.x & 63) {}
-
-  __device__ __forceinline__ void begin(int tmat, int row0, int col0, bool mir) {
-    row_w0 = row0; col_w0 = col0; mirror = mir;
-    const int mi = a.members ? a.members[tmat] : tmat;
-    post = 1.0f;
-    if (a.post == POST_INV) post = a.scales[mi].inv;
-    else if (a.post == POST_INV2) post = a.scales[mi].inv2;
-    E = a.E ? static_cast<const bf16_t*>(a.E) + (size_t)tmat * a.strideE : nullptr;
-    C = static_cast<bf16_t*>(a.C) + (size_t)tmat * a.strideC;
-    update = UPD;
-    wm_real = wn_real = w_is_bf16 = 0;
-    skip_w = true;
-    wptr = nullptr;
-    if constexpr (UPD) {
-      const MatStatic& ms = a.stat[mi];
-      wm_real = ms.m; wn_real = ms.n; w_is_bf16 = ms.w_dtype;
-      wptr = a.dyn[mi].w;
-      skip_w = (a.scales[mi].status & 2u) != 0;
-    }
-    w_pref = update && !skip_w && w_is_bf16 && (wn_real % CH) == 0;
-  }
-
-  // first row of band b inside the wavefront tile: MFMA block b / 4, row group b % 4
-  static __device__ __forceinline__ constexpr int band_row(int b) { return (b >> 2) * 32 + (b & 3) * 8; }
-
-  template <int BAND>
-  __device__ __forceinline__ void prefetch() {
-    constexpr int slot = BAND % NPF;
-    const int grow = row_w0 + band_row(BAND) + (lane >> 3), gcol = col_w0 + (lane & 7) * CH;
-    if (E != nullptr) ev[slot] = *reinterpret_cast<const bf16x8*>(E + (size_t)grow * a.lde + gcol);
-    if constexpr (UPD) {
-      if (w_pref && grow < wm_real && gcol + CH <= wn_real)
-        wv[slot] = *reinterpret_cast<const bf16x8*>(static_cast<const bf16_t*>(wptr) + (size_t)grow * wn_real + gcol);
-    }
-  }
-  // the first NPRE bands are requested while the last K steps are still being multiplied (few, the
-  // fragment registers are still live then); the rest of the ring at the start of run()
-  __device__ __forceinline__ void prefetch_first() {
-    static_for<NPRE>([&](auto b) { prefetch<b>(); });
-  }
-
-  // prefetch_first() must have been called.  stage: 8 x LDW floats private to this wavefront.
-  __device__ __forceinline__ void run(f32x16 (&acc)[MI][NI], float* __restrict__ stage) {
-    static_assert(NPRE <= NPF && BANDS % NPF == 0, "bands are fetched in batches of NPF");
-    // With loads and stores in flight together the load counter cannot be waited on selectively
-    // (stores retire out of order), so every wait drains everything.  Operands are therefore fetched
-    // a batch of NPF bands at a time: one memory latency per batch instead of one per band.
-    static_for<NPF - NPRE>([&](auto b) { prefetch<NPRE + b>(); });
-    static_for<BANDS>([&](auto b) {
-      constexpr int slot = b % NPF;
-      if constexpr (b > 0 && b % NPF == 0) static_for<NPF>([&](auto q) { prefetch<b + q>(); });
-      constexpr int i = b >> 2, vg = b & 3;
-      wave_sync();         // previous band fully consumed
-      static_for<NI>([&](auto j) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-          stage[((lane >> 5) * 4 + e) * LDW + j * 32 + (lane & 31)] = acc[i][j][vg * 4 + e];
-      });
-      wave_sync();
-      const int r = lane >> 3, ch = lane & 7;
-      const int grow = row_w0 + band_row(b) + r, gcol = col_w0 + ch * CH;
-      float val[CH];
-      {
-        const f32x4* src = reinterpret_cast<const f32x4*>(stage + r * LDW + ch * CH);
-        const f32x4 t0 = src[0], t1 = src[1];
-        val[0] = t0.x; val[1] = t0.y; val[2] = t0.z; val[3] = t0.w;
-        val[4] = t1.x; val[5] = t1.y; val[6] = t1.z; val[7] = t1.w;
-      }
-      if (E != nullptr) {
-#pragma unroll
-        for (int e = 0; e < CH; ++e) val[e] = post * (a.alpha * val[e] + a.beta * (float)ev[slot][e]);
-      } else {
-#pragma unroll
-        for (int e = 0; e < CH; ++e) val[e] = post * (a.alpha * val[e]);
-      }
-      bf16x8 ov;
-#pragma unroll
-      for (int e = 0; e < CH; ++e) ov[e] = (bf16_t)val[e];
-      if (!update || a.store_out) *reinterpret_cast<bf16x8*>(C + (size_t)grow * a.ldc + gcol) = ov;
-      if (mirror) {
-        // keep the rounded result for the transposed store below
-        f32x4* dst = reinterpret_cast<f32x4*>(stage + r * LDW + ch * CH);
-        dst[0] = f32x4{(float)ov[0], (float)ov[1], (float)ov[2], (float)ov[3]};
-        dst[1] = f32x4{(float)ov[4], (float)ov[5], (float)ov[6], (float)ov[7]};
-      }
-      if (UPD && !skip_w && grow < wm_real) {
-        // W <- (1 - eta lambda) W - eta gamma O, O as stored in the working precision
-        const size_t wi = (size_t)grow * wn_real + gcol;
-        if (w_pref && gcol + CH <= wn_real) {
-          bf16x8 w_in = wv[UPD ? slot : 0];
-#pragma unroll
-          for (int e = 0; e < CH; ++e) w_in[e] = (bf16_t)(a.w_keep * (float)w_in[e] - a.o_scale * (float)ov[e]);
-          *reinterpret_cast<bf16x8*>(static_cast<bf16_t*>(wptr) + wi) = w_in;
-        } else {
-#pragma unroll
-          for (int e = 0; e < CH; ++e) {
-            if (gcol + e < wn_real) {
-              if (w_is_bf16) {
-                bf16_t* w = static_cast<bf16_t*>(wptr) + wi + e;
-                *w = (bf16_t)(a.w_keep * (float)*w - a.o_scale * (float)ov[e]);
-              } else {
-                float* w = static_cast<float*>(wptr) + wi + e;
-                *w = a.w_keep * *w - a.o_scale * (float)ov[e];
-              }
-            }
-          }
-        }
-      }
-      if (mirror) {
-        // transposed copy of this band: C[col][8 consecutive rows], one 16-byte store per lane
-        wave_sync();
-        bf16x8 tv;
-#pragma unroll
-        for (int e = 0; e < CH; ++e) tv[e] = (bf16_t)stage[e * LDW + lane];
-        *reinterpret_cast<bf16x8*>(C + (size_t)(col_w0 + lane) * a.ldc + row_w0 + band_row(b)) = tv;
-      }
-    });
-  }
-};
-
 #define MONA_AS3_EPI __attribute__((address_space(3)))
 // Eight transposed LDS reads (4 rows x 16 columns of bf16 per group of 16 lanes and read), 1024 bytes =
 // 4 staged rows apart, then one wait.  A free function: an asm statement cannot name variables captured
@@ -545,7 +403,7 @@ __device__ __forceinline__ void tr_read_32_rows(u32x2 (&lo)[4], u32x2 (&hi)[4], 
 // group of four registers, four CONSECUTIVE columns, so a whole block row (32 rows x 64 columns of this
 // wavefront) is staged with 8 ds_write_b128 instead of 32 ds_write_b32.  Four passes of 8 rows x 64
 // columns follow, each lane reading 8 consecutive floats back: one 16-byte chunk of E, of C and (fused
-// update) of W per lane and pass, exactly the global access pattern of FineEpilogue.
+// update) of W per lane and pass.
 // Staging area per wavefront: 32 rows of 256 bytes (no padding; the 16-byte chunk index is XORed with
 // row % 16, which spreads both the column-wise writes and the row-wise reads over all banks).
 // Mirrored (symmetric) tiles: each pass leaves its rounded bf16 row in the 256 bytes of the fp32 row it
@@ -825,10 +683,8 @@ __global__ __launch_bounds__(kThreads) void ns_gemm_bf16_kernel(const GemmArgs a
 // ---- bf16 kernel, direct-to-LDS pipeline ------------------------------------------------------
 // Block tile BM x BN, WGM x WGN wavefronts of 128 x 64 each, K step 32, a ring of STAGES LDS
 // stages filled straight from global memory (global_load_lds, 16 bytes per lane, no staging
-// registers).  Two configurations are built:
-//   256 x 128, 4 wavefronts, 3 stages (72 KB LDS): two workgroups share a CU, so one multiplies
-//       while the other is in its prologue, epilogue or at a barrier;
-//   256 x 256, 8 wavefronts, 4 stages (128 KB LDS): one workgroup per CU, two wavefronts per SIMD.
+// registers): 256 x 256, 8 wavefronts, 4 stages (128 KB LDS), one workgroup per CU, two wavefronts
+// per SIMD.
 //
 // LDS layouts of one R x 32 operand tile, in 16-byte chunks:
 //   row-major operand (K contiguous in memory): R rows x 4 chunks, chunk c of row r at
@@ -922,13 +778,9 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
   static_assert(NLP * 64 * NW == P_U && NLQ * 64 * NW == Q_U, "tiles must split evenly over the wavefronts");
   constexpr int kStageFloats = NW * 32 * (WN + 4);
   static_assert(kStageFloats * 4 <= STAGES * STAGE_U * 16, "epilogue staging must fit in the operand ring");
-#ifdef MONA_FINE_EPILOGUE
-  constexpr int LDS_U = STAGES * STAGE_U;
-#else
   // the ring, and behind it what the epilogue's staging needs beyond the last stage
   constexpr int LDS_U = STAGES * STAGE_U + (NW * 8192 / 16 - STAGE_U);
   static_assert(LDS_U * 16 <= 160 * 1024, "LDS of one CU");
-#endif
   __shared__ __attribute__((aligned(256))) u32x4 lds[LDS_U];
 
   MONA_STAMP(0);
@@ -1055,13 +907,9 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
   auto multiply = [&](auto slot) {
     static_for<MI>([&](auto i) {
       static_for<NI>([&](auto j) {
-#ifdef MONA_FINE_EPILOGUE
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i].get(), fb[slot][j].get(), acc[i][j], 0, 0, 0);
-#else
         // operand roles swapped: the block is accumulated transposed (lane = output row), which is the
         // layout the epilogue stages with 16-byte LDS writes
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[slot][j].get(), fa[slot][i].get(), acc[i][j], 0, 0, 0);
-#endif
       });
     });
   };
@@ -1092,20 +940,12 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
   };
 
   static_assert(STAGES == 4, "the pipeline below is written for a ring of 4 stages");
-#ifdef MONA_FINE_EPILOGUE
-  typedef FineEpilogue<MI, NI, /*batch*/ (UPD ? 4 : 8), /*early*/ 2, UPD> Epi;
-  Epi epi(a);
-  static_assert(NW * Epi::kStageFloatsPerWave * 4 <= STAGE_U * 16, "epilogue staging must fit in the last stage");
-  // epilogue staging lives in stage 3, which the next tile's early loads (stages 0..2) leave alone
-  float* const stage_f = reinterpret_cast<float*>(lds + 3 * STAGE_U) + wave * Epi::kStageFloatsPerWave;
-#else
   typedef BlockEpilogue<MI, /*batch*/ (UPD ? 8 : 16), /*early*/ 2, UPD, HAS_E> Epi;
   Epi epi(a);
   static_assert(NI == Epi::NI && (3 * STAGE_U * 16 + NW * Epi::kStageBytesPerWave) <= LDS_U * 16,
                 "epilogue staging: stage 3 and the LDS behind the ring");
   // epilogue staging starts at stage 3, which the next tile's early loads (stages 0..2) leave alone
   char* const stage_f = reinterpret_cast<char*>(lds + 3 * STAGE_U) + wave * Epi::kStageBytesPerWave;
-#endif
 
   TileId t = tile_at(0);
   if (!t.valid) return;
@@ -1306,9 +1146,6 @@ static void dma_debug_report(const GemmArgs& a, bool transP, bool transQ, int gr
 #endif
 }
 
-// development switch: MONA_GEMM_V1=1 selects the register-staged 256-tile kernel
-static const bool g_use_v2 = []() { const char* e = getenv("MONA_GEMM_V1"); return !(e && e[0] == '1'); }();
-
 hipError_t launch_ns_gemm(const GemmArgs& a, int tile, bool transP, bool transQ, bool f32, hipStream_t s) {
   const long long total = (long long)a.tiles_per_mat * a.count;
   if (total <= 0) return hipSuccess;
@@ -1322,7 +1159,7 @@ hipError_t launch_ns_gemm(const GemmArgs& a, int tile, bool transP, bool transQ,
     else return hipErrorInvalidValue;
     return hipGetLastError();
   }
-  if (tile == 256 && a.tile_n == 256 && g_use_v2) {
+  if (tile == 256 && a.tile_n == 256) {
     // persistent: one workgroup per CU walks its share of the tiles
     static const int num_cus = []() {
       int dev = 0, n = 0;
@@ -1346,7 +1183,6 @@ hipError_t launch_ns_gemm(const GemmArgs& a, int tile, bool transP, bool transQ,
     dma_debug_report(a, transP, transQ, pgrid, total);
     return hipGetLastError();
   }
-  if (tile == 256) return launch_bf16<256, 256>(a, transP, transQ, grid, s);
   if (tile == 128) return launch_bf16<128, 128>(a, transP, transQ, grid, s);
   return hipErrorInvalidValue;
 }
