@@ -161,6 +161,7 @@ def main() -> int:
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB elementwise copy (negation; a reference kernel of known traffic for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--ns-steps", type=int, default=5, help="Newton-Schulz iterations T (the paper's 5)")
     ap.add_argument("--streams", type=int, default=0,
                     help="streams the shape groups' launch chains are spread over (0 = library default, 1 = one)")
     ap.add_argument("--graph", action="store_true",
@@ -190,7 +191,7 @@ def main() -> int:
     torch.cuda.set_device(dev)
     workload = wl.WORKLOADS[args.workload]
     widx = list(wl.WORKLOADS).index(args.workload)
-    hp = wl.HParams(flags=B.MONA_FLAG_MUON_ONLY if args.muon_only else 0)
+    hp = wl.HParams(flags=B.MONA_FLAG_MUON_ONLY if args.muon_only else 0, ns_steps=args.ns_steps)
     shapes = workload.shapes()
     g_dtype = torch.float32 if args.g_dtype == "f32" else torch.bfloat16
     state_dtype = torch.float32 if args.state_dtype == "f32" else torch.bfloat16
