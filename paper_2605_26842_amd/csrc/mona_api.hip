@@ -210,7 +210,10 @@ void build_layout(const mona_matrix* mats, int count, const mona_options& opt, L
 
 constexpr int kRing = 4;
 constexpr int kDefaultLanes = 4;   // streams the shape groups of one step are spread over
-constexpr long long kBigLaunchTiles = 512;   // launches of at least this many tiles fill 256 CUs twice over
+// launches of at least this many tiles keep 256 CUs busy for six rounds or more.  Measured: with the limit at
+// 512 or 768 mid-sized groups (a bank of 64 experts of 1024 x 2048) lose 4 % by waiting for each other; at
+// 3072 the two expert groups of a 128-expert layer run side by side and lose 5 % to each other's L2 traffic.
+constexpr long long kBigLaunchTiles = 1536;
 
 struct LaunchRecord {
   int kind, group, iter, tile;
@@ -463,7 +466,7 @@ int mona_init_state(const mona_matrix* mats, int32_t count, const mona_options* 
   for (auto& e : st->ev) INIT_TRY(hipEventCreate(&e));
   st->ev_valid = true;
   {
-    // Lanes.  A group whose every launch covers the chip several times over gains nothing from company
+    // Lanes.  A group whose every launch covers the chip many times over gains nothing from company
     // (two persistent kernels sharing the CUs only disturb each other's L2 reuse: measured slower), so
     // such groups stay in a row on the caller's stream; the others, sorted by work, each go to the
     // least loaded lane.

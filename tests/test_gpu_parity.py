@@ -426,8 +426,9 @@ def test_mixed_large_and_small_groups_on_several_streams():
     kernels: every lane's result against the oracle, and the same bits as a single-stream run."""
     say("[case] mixed lanes")
     dev = "cuda:0"
-    shapes = [(1024, 2048)] * 52 + [(512, 4096)] * 2 + [(768, 768)] + [(4096, 512)] * 2 + [(100, 300), (40, 64)]
-    sample = [3, 52, 54, 55, 57, 58]
+    shapes = [(1024, 2048)] * 156 + [(512, 4096)] * 2 + [(768, 768)] + [(4096, 512)] * 2 + [(100, 300), (40, 64)]
+    big = 156           # 156 x 10 Gram tiles = 1560: a group that keeps the caller's stream to itself
+    sample = [3, big, big + 2, big + 3, big + 5, big + 6]
     weights = [wl.draw_weight(s, 9000 + i, torch.bfloat16, dev) for i, s in enumerate(shapes)]
     grads = [[wl.GradientStream(s, 9500 + i, dev).next() for i, s in enumerate(shapes)] for _ in range(2)]
     hp = wl.HParams()
@@ -444,9 +445,9 @@ def test_mixed_large_and_small_groups_on_several_streams():
     for gs in grads:
         opt1.step(gs, hp)
     torch.cuda.synchronize()
-    for i in range(52):
+    for i in range(big):
         assert torch.equal(w1[i], dev_w[i]), f"matrix {i}: one stream and several streams disagree"
-    for i in range(52, len(shapes)):
+    for i in range(big, len(shapes)):
         d = (w1[i].float() - dev_w[i].float()).norm() / (dev_w[i].float().norm() + 1e-30)
         assert float(d) <= 1e-3, (i, float(d))
 
