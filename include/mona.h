@@ -110,6 +110,11 @@ typedef struct mona_options {
 
 #define MONA_ACCEL_TWO_BUFFER 0
 #define MONA_ACCEL_ONE_BUFFER 1
+/* The streaming variant as Sec. 6.3 describes it: the arithmetic of Alg. 1 unchanged, but the library
+ * keeps no G_{k-1} of its own -- the difference is taken against a gradient slot the CALLER keeps from
+ * step to step, and the slot is overwritten with G_k.  Steps of such a state go through
+ * mona_step_streaming(); the saving is memory (one state array less), not traffic. */
+#define MONA_ACCEL_CALLER_SLOT 2
 
 typedef struct mona_state mona_state;   /* opaque, HOST */
 
@@ -145,12 +150,22 @@ int mona_init_state(const mona_matrix* mats, int32_t count, const mona_options* 
 int mona_step(mona_state* st, const mona_matrix* mats, int32_t count,
               const mona_hparams* hp, void* stream);
 
+/* The step of a state built with MONA_ACCEL_CALLER_SLOT (Sec. 6.3, streaming gradient computation).
+ *   slots  HOST array of `count` DEVICE pointers; slots[i] is an m x n array of the state dtype
+ *          (mona_options.state_dtype), 16-byte aligned, owned by the caller, which must keep its
+ *          contents from one step to the next: it holds G_{k-1} on entry (all zero before the
+ *          first step: Alg. 1 starts from G_0 = 0) and G_k on return.
+ * Everything else as mona_step; mona_step itself returns MONA_EINVAL on such a state, and this
+ * function does on any other. */
+int mona_step_streaming(mona_state* st, const mona_matrix* mats, void* const* slots, int32_t count,
+                        const mona_hparams* hp, void* stream);
+
 /* Release host bookkeeping (waits for the state's pinned tables to be idle).  The arena
  * is not touched. */
 int mona_free_state(mona_state* st);
 
 typedef enum mona_view_kind {
-  MONA_VIEW_G_PREV = 0,  /* G_{k-1}: m x n, state dtype                                */
+  MONA_VIEW_G_PREV = 0,  /* G_{k-1}: m x n, state dtype (MONA_EUNSUPPORTED when the caller keeps it) */
   MONA_VIEW_A = 1,       /* A_k:     m x n, state dtype                                */
   MONA_VIEW_M = 2,       /* M_k:     m x n, fp32                                       */
   MONA_VIEW_NORM = 3,    /* ||M_k||_F of the last step: 1 x 1 fp32                      */

@@ -21,11 +21,11 @@ MONA_OK, MONA_EINVAL, MONA_ESHAPE, MONA_ENOMEM, MONA_EHIP, MONA_EUNSUPPORTED = 0
 MONA_F32, MONA_BF16 = 0, 1
 MONA_FLAG_FIRST_DIFF_ZERO, MONA_FLAG_KEEP_O, MONA_FLAG_MUON_ONLY = 0x1, 0x2, 0x4
 MONA_VIEW_G_PREV, MONA_VIEW_A, MONA_VIEW_M, MONA_VIEW_NORM, MONA_VIEW_O, MONA_VIEW_C = 0, 1, 2, 3, 4, 5
-MONA_ACCEL_TWO_BUFFER, MONA_ACCEL_ONE_BUFFER = 0, 1
+MONA_ACCEL_TWO_BUFFER, MONA_ACCEL_ONE_BUFFER, MONA_ACCEL_CALLER_SLOT = 0, 1, 2
 MONA_STATUS_ZERO_NORM, MONA_STATUS_NONFINITE = 0x1, 0x2
 
 EXPORTED = (
-    "mona_state_size", "mona_init_state", "mona_step", "mona_free_state", "mona_state_view",
+    "mona_state_size", "mona_init_state", "mona_step", "mona_step_streaming", "mona_free_state", "mona_state_view",
     "mona_state_export_size", "mona_state_export", "mona_state_import", "mona_state_step_count",
     "mona_state_status", "mona_set_profiling", "mona_last_step_times", "mona_last_step_launches",
     "mona_plan_info", "mona_last_error", "mona_version",
@@ -98,6 +98,7 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.mona_state_size.argtypes = [P(mona_matrix), i32, P(mona_options), P(sz)]
     lib.mona_init_state.argtypes = [P(mona_matrix), i32, P(mona_options), vp, sz, vp, P(vp)]
     lib.mona_step.argtypes = [vp, P(mona_matrix), i32, P(mona_hparams), vp]
+    lib.mona_step_streaming.argtypes = [vp, P(mona_matrix), P(vp), i32, P(mona_hparams), vp]
     lib.mona_free_state.argtypes = [vp]
     lib.mona_state_view.argtypes = [vp, i32, i32, P(mona_view)]
     lib.mona_state_export_size.argtypes = [vp, P(sz)]
@@ -186,6 +187,10 @@ def mona_step(state: int, mats, count: int, hp: mona_hparams, stream: int) -> No
     _check(load_library().mona_step(state, mats, count, C.byref(hp), stream))
 
 
+def mona_step_streaming(state: int, mats, slots, count: int, hp: mona_hparams, stream: int) -> None:
+    _check(load_library().mona_step_streaming(state, mats, slots, count, C.byref(hp), stream))
+
+
 def mona_free_state(state: int) -> None:
     _check(load_library().mona_free_state(state))
 
@@ -238,14 +243,23 @@ class MonaOptimizer:
     def _stream(self) -> int:
         return torch.cuda.current_stream(self.device).cuda_stream
 
-    def step(self, grads: Sequence[torch.Tensor], hp) -> None:
-        """One MONA step over all matrices (asynchronous on torch's current stream)."""
+    def step(self, grads: Sequence[torch.Tensor], hp, slots: Optional[Sequence[torch.Tensor]] = None) -> None:
+        """One MONA step over all matrices (asynchronous on torch's current stream).  `slots`: the
+        caller-kept previous-gradient arrays of a MONA_ACCEL_CALLER_SLOT state."""
         key = tuple(g.data_ptr() for g in grads)
         if key != self._mats_key:
             self._mats = make_matrices(self.weights, grads)
             self._mats_key = key
         hpc = hp if isinstance(hp, mona_hparams) else make_hparams(hp)
-        mona_step(self.state, self._mats, self.count, hpc, self._stream())
+        if slots is None:
+            mona_step(self.state, self._mats, self.count, hpc, self._stream())
+            return
+        arr = (C.c_void_p * self.count)()
+        for i, t in enumerate(slots):
+            if t.shape != self.weights[i].shape or not t.is_contiguous() or t.dtype != self.state_dtype:
+                raise ValueError(f"slot {i}: must be contiguous, shaped like the parameter, of the state dtype")
+            arr[i] = t.data_ptr()
+        mona_step_streaming(self.state, self._mats, arr, self.count, hpc, self._stream())
 
     # ---- views of the state as torch tensors (no copy) ----
     def view(self, i: int, kind: int) -> torch.Tensor:

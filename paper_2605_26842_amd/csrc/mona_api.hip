@@ -73,6 +73,7 @@ struct Layout {
   int count = 0;
   int ssize = 4;             // bytes per element of the stored G_{k-1}, A (or C)
   bool one_buffer = false;   // no G_{k-1}; acc_off holds C
+  bool caller_slot = false;  // G_{k-1} is kept by the caller (streaming variant)
   std::vector<size_t> gprev_off, acc_off, mom_off;
   size_t state_begin = 0, state_bytes = 0;     // persistent {G_prev, A, M}
   size_t work_begin = 0, work_bytes = 0;       // X, S, B of every group (zeroed once)
@@ -111,8 +112,9 @@ int check_opts(const mona_options* o, mona_options* out) {
   if (z.ns_precision != 0 && z.ns_precision != 1) return fail(MONA_EINVAL, "ns_precision must be 0 or 1");
   if (z.state_dtype != MONA_F32 && z.state_dtype != MONA_BF16)
     return fail(MONA_EINVAL, "state_dtype must be MONA_F32 or MONA_BF16");
-  if (z.accel_form != MONA_ACCEL_TWO_BUFFER && z.accel_form != MONA_ACCEL_ONE_BUFFER)
-    return fail(MONA_EINVAL, "accel_form must be MONA_ACCEL_TWO_BUFFER or MONA_ACCEL_ONE_BUFFER");
+  if (z.accel_form != MONA_ACCEL_TWO_BUFFER && z.accel_form != MONA_ACCEL_ONE_BUFFER &&
+      z.accel_form != MONA_ACCEL_CALLER_SLOT)
+    return fail(MONA_EINVAL, "accel_form must be MONA_ACCEL_TWO_BUFFER, MONA_ACCEL_ONE_BUFFER or MONA_ACCEL_CALLER_SLOT");
   if (z.max_streams < 0 || z.max_streams > 8) return fail(MONA_EINVAL, "max_streams must lie in [0, 8]");
   for (int r : z.reserved)
     if (r != 0) return fail(MONA_EINVAL, "reserved option fields must be 0");
@@ -124,6 +126,7 @@ void build_layout(const mona_matrix* mats, int count, const mona_options& opt, L
   L.count = count;
   L.ssize = opt.state_dtype == MONA_BF16 ? 2 : 4;
   L.one_buffer = opt.accel_form == MONA_ACCEL_ONE_BUFFER;
+  L.caller_slot = opt.accel_form == MONA_ACCEL_CALLER_SLOT;
   size_t off = 0;
   // persistent state, contiguous: this block is what checkpoints carry
   L.state_begin = off;
@@ -133,7 +136,7 @@ void build_layout(const mona_matrix* mats, int count, const mona_options& opt, L
   for (int i = 0; i < count; ++i) {
     const size_t ne = (size_t)mats[i].m * mats[i].n;
     L.gprev_off[i] = off;
-    if (!L.one_buffer) off = align_up(off + ne * L.ssize);
+    if (!L.one_buffer && !L.caller_slot) off = align_up(off + ne * L.ssize);
     L.acc_off[i] = off;   off = align_up(off + ne * L.ssize);
     L.mom_off[i] = off;   off = align_up(off + ne * 4);
   }
@@ -533,7 +536,7 @@ int mona_init_state(const mona_matrix* mats, int32_t count, const mona_options* 
     const Group& g = L.groups[L.group_of[i]];
     MatStatic& ms = stat[i];
     memset(&ms, 0, sizeof ms);
-    ms.g_prev = L.one_buffer ? nullptr : st->arena + L.gprev_off[i];
+    ms.g_prev = (L.one_buffer || L.caller_slot) ? nullptr : st->arena + L.gprev_off[i];
     ms.acc = st->arena + L.acc_off[i];
     ms.mom = reinterpret_cast<float*>(st->arena + L.mom_off[i]);
     ms.x = st->arena + g.x_off[0] + (size_t)L.rank_in_group[i] * g.x_stride * g.esize;
@@ -563,8 +566,42 @@ int mona_init_state(const mona_matrix* mats, int32_t count, const mona_options* 
   return MONA_OK;
 }
 
+}  // extern "C"
+
+namespace {
+int step_impl(mona_state* st, const mona_matrix* mats, void* const* slots, int32_t count, const mona_hparams* hp,
+              void* stream);
+}
+
+extern "C" {
+
 int mona_step(mona_state* st, const mona_matrix* mats, int32_t count, const mona_hparams* hp, void* stream) {
   if (!st) return fail(MONA_EINVAL, "state is NULL");
+  if (st->L.caller_slot)
+    return fail(MONA_EINVAL, "this state keeps no G_{k-1} (MONA_ACCEL_CALLER_SLOT): use mona_step_streaming");
+  return step_impl(st, mats, nullptr, count, hp, stream);
+}
+
+int mona_step_streaming(mona_state* st, const mona_matrix* mats, void* const* slots, int32_t count,
+                        const mona_hparams* hp, void* stream) {
+  if (!st) return fail(MONA_EINVAL, "state is NULL");
+  if (!st->L.caller_slot)
+    return fail(MONA_EINVAL, "mona_step_streaming needs a state built with MONA_ACCEL_CALLER_SLOT");
+  if (!slots) return fail(MONA_EINVAL, "slots is NULL");
+  if (count == st->L.count)
+    for (int i = 0; i < count; ++i) {
+      if (!slots[i]) return fail(MONA_EINVAL, "slot %d is NULL", i);
+      if ((uintptr_t)slots[i] & 15) return fail(MONA_EINVAL, "slot %d must be 16-byte aligned", i);
+    }
+  return step_impl(st, mats, slots, count, hp, stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+int step_impl(mona_state* st, const mona_matrix* mats, void* const* slots, int32_t count, const mona_hparams* hp,
+              void* stream) {
   int rc = check_mats(mats, count, true);
   if (rc) return rc;
   rc = check_hparams(hp);
@@ -592,7 +629,8 @@ int mona_step(mona_state* st, const mona_matrix* mats, int32_t count, const mona
   bool changed = !st->dyn_valid;
   if (!changed)
     for (int i = 0; i < count; ++i)
-      if (st->last_dyn[i].w != mats[i].w || st->last_dyn[i].g != mats[i].g) { changed = true; break; }
+      if (st->last_dyn[i].w != mats[i].w || st->last_dyn[i].g != mats[i].g ||
+          st->last_dyn[i].slot != (slots ? slots[i] : nullptr)) { changed = true; break; }
   if (changed) {
     const int slot = st->ring_next;
     if (st->ring_used[slot]) HIP_TRY(hipEventSynchronize(st->ring_ev[slot]));
@@ -600,6 +638,7 @@ int mona_step(mona_state* st, const mona_matrix* mats, int32_t count, const mona
     for (int i = 0; i < count; ++i) {
       st->last_dyn[i].w = mats[i].w;
       st->last_dyn[i].g = mats[i].g;
+      st->last_dyn[i].slot = slots ? slots[i] : nullptr;
       st->ring[slot][i] = st->last_dyn[i];
     }
     HIP_TRY(hipMemcpyAsync(st->arena + L.dyn_off, st->ring[slot], sizeof(MatDynamic) * count, hipMemcpyHostToDevice,
@@ -694,6 +733,10 @@ int mona_step(mona_state* st, const mona_matrix* mats, int32_t count, const mona
   return MONA_OK;
 }
 
+}  // namespace
+
+extern "C" {
+
 int mona_free_state(mona_state* st) {
   if (!st) return MONA_OK;
   for (int i = 0; i < kRing; ++i) {
@@ -719,6 +762,7 @@ int mona_state_view(mona_state* st, int32_t i, int32_t kind, mona_view* out) {
   switch (kind) {
     case MONA_VIEW_G_PREV:
       if (L.one_buffer) return fail(MONA_EUNSUPPORTED, "the one-buffer form stores no G_{k-1}");
+      if (L.caller_slot) return fail(MONA_EUNSUPPORTED, "G_{k-1} is kept by the caller (MONA_ACCEL_CALLER_SLOT)");
       out->ptr = st->arena + L.gprev_off[i]; out->dtype = st->opt.state_dtype; break;
     case MONA_VIEW_A:
       if (L.one_buffer) return fail(MONA_EUNSUPPORTED, "the one-buffer form stores C, not A (use MONA_VIEW_C)");

@@ -11,7 +11,7 @@ typedef __bf16 bf16_t;
 
 // Static per-matrix description, uploaded once when the state is built.
 struct MatStatic {
-  void* g_prev;        // G_{k-1}, state dtype (NULL in the one-buffer form)
+  void* g_prev;        // G_{k-1}, state dtype (NULL in the one-buffer form and when the caller keeps it)
   void* acc;           // A_k (or, in the one-buffer form, C_{k+1}), state dtype
   float* mom;          // M_k, fp32
   void* x;             // where the Newton-Schulz input (M_k, unscaled) is written: bf16 or fp32
@@ -27,6 +27,7 @@ struct MatStatic {
 struct MatDynamic {
   void* w;
   const void* g;
+  void* slot;          // caller-kept G_{k-1} (streaming variant), else NULL
 };
 
 // Result of the per-matrix Frobenius norm (Sec. 3.2, X_0 = M / ||M||_F).

@@ -103,7 +103,8 @@ __global__ __launch_bounds__(kEwThreads) void state_update_kernel(
   const BlockWork bw = work[blockIdx.x];
   const MatStatic ms = stat[bw.mat];
   const GT* __restrict__ g = static_cast<const GT*>(dyn[bw.mat].g);
-  ST* __restrict__ gp = static_cast<ST*>(ms.g_prev);
+  // G_{k-1} lives in the arena, or (streaming variant) in the slot the caller keeps
+  ST* __restrict__ gp = static_cast<ST*>(ms.g_prev ? ms.g_prev : dyn[bw.mat].slot);
   ST* __restrict__ ac = static_cast<ST*>(ms.acc);
   float* __restrict__ mo = ms.mom;
   // working copy of M_k for the matrix products: bf16, or fp32 for matrices orthogonalised in fp32

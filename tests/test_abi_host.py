@@ -53,6 +53,9 @@ def test_state_size_accounts_for_state_and_workspace():
     assert one - single == n * 4
     single_lite = B.mona_state_size(shapes((256, 512)), 1, B.mona_options(0, B.MONA_BF16, B.MONA_ACCEL_ONE_BUFFER))
     assert one - single_lite == n * 4 + n * 2           # 6 instead of 12 state bytes per element
+    # streaming variant: the caller keeps G_{k-1}, the arena is as small as the one-buffer form's
+    kept = B.mona_state_size(shapes((256, 512)), 1, B.mona_options(0, B.MONA_F32, B.MONA_ACCEL_CALLER_SLOT))
+    assert kept == single
     # padding: 100 x 300 works on 128 x 384 copies
     rag = B.mona_state_size(shapes((100, 300)), 1)
     assert rag >= 100 * 300 * 12 + 2 * 128 * 384 * 2 + 2 * 128 * 128 * 2
@@ -82,7 +85,7 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert rc == B.MONA_EINVAL
     rc, _ = rc_of(lib.mona_state_size, shapes((4, 4)), 1, C.byref(B.mona_options(2, 0)), C.byref(out))
     assert rc == B.MONA_EINVAL
-    rc, msg = rc_of(lib.mona_state_size, shapes((4, 4)), 1, C.byref(B.mona_options(0, 0, 2)), C.byref(out))
+    rc, msg = rc_of(lib.mona_state_size, shapes((4, 4)), 1, C.byref(B.mona_options(0, 0, 3)), C.byref(out))
     assert rc == B.MONA_EINVAL and "accel_form" in msg
     rc, msg = rc_of(lib.mona_state_size, shapes((4, 4)), 1,
                     C.byref(B.mona_options(0, 0, 0, 0, (C.c_int32 * 4)(0, 0, 1, 0))), C.byref(out))
@@ -103,6 +106,7 @@ def test_bad_arguments_are_rejected_on_the_host():
     # step / view / free on a NULL state
     hp = B.mona_hparams()
     assert lib.mona_step(None, shapes((4, 4)), 1, C.byref(hp), None) == B.MONA_EINVAL
+    assert lib.mona_step_streaming(None, shapes((4, 4)), None, 1, C.byref(hp), None) == B.MONA_EINVAL
     assert lib.mona_state_view(None, 0, 0, None) == B.MONA_EINVAL
     assert lib.mona_free_state(None) == B.MONA_OK
     with pytest.raises(B.MonaError):

@@ -228,6 +228,57 @@ def test_one_buffer_form_of_the_acceleration_term(state_dtype):
     assert ei.value.code == B.MONA_EINVAL and opt.step_count() == 4
 
 
+@pytest.mark.parametrize("state_dtype", [torch.float32, torch.bfloat16])
+def test_streaming_gradient_with_caller_kept_slots(state_dtype):
+    """Sec. 6.3's streaming variant: the library holds no G_{k-1}; it differences against the slot the
+    caller keeps and leaves G_k there.  Same arithmetic as Alg. 1, so the oracle of Alg. 1 is the
+    reference, and the stored-G_{k-1} GPU path must agree bit for bit."""
+    lite = state_dtype == torch.bfloat16
+    say("[case] streaming gradient, caller-kept slots, state", state_dtype)
+    w, weights, grads = inputs("ragged_mix", steps=4)
+    hp = dataclasses.replace(wl.HParams(), flags=B.MONA_FLAG_KEEP_O)
+    watch = list(range(len(weights)))
+    dev_w = [x.to("cuda:0").contiguous() for x in weights]
+    opt = B.MonaOptimizer(dev_w, state_dtype=state_dtype, g_dtype=grads[0][0].dtype,
+                          accel_form=B.MONA_ACCEL_CALLER_SLOT)
+    slots = [torch.zeros(x.shape, dtype=state_dtype, device="cuda:0") for x in weights]
+    hist = []
+    for gk in grads:
+        dev_g = [g.to("cuda:0").contiguous() for g in gk]
+        before = {i: H.f64(dev_w[i]) for i in watch}
+        opt.step(dev_g, hp, slots=slots)
+        torch.cuda.synchronize()
+        hist.append({i: H.Snapshot(H.f64(slots[i]), H.f64(opt.accel(i)), None, H.f64(opt.momentum(i)),
+                                   float(opt.norm(i).item()), H.f64(opt.last_o(i)), H.f64(dev_w[i]), before[i])
+                     for i in watch})
+    worst = H.check_history(weights, grads, hp, hist, watch, H.TOL_NS_BF16,
+                            state_tol=2.0 ** -7 if lite else H.TOL_STATE,
+                            state_dtype="bf16" if lite else "f32", label="caller-slot")
+    say("[worst]", worst)
+    # bit-identical to the path that stores G_{k-1} itself
+    opt2, dev_w2, hist2 = H.run_gpu(weights, grads, hp, 0, state_dtype=state_dtype)
+    for i in watch:
+        assert torch.equal(dev_w[i], dev_w2[i])
+        assert torch.equal(opt.momentum(i), opt2.momentum(i)) and torch.equal(opt.accel(i), opt2.accel(i))
+        assert torch.equal(slots[i], opt2.g_prev(i))
+    assert opt2.arena_bytes - opt.arena_bytes >= sum(x.numel() for x in weights) * slots[0].element_size()
+    # the array the caller keeps has no view; the plain entry point refuses such a state, and
+    # the streaming one refuses a state that stores G_{k-1} itself
+    with pytest.raises(B.MonaError) as ei:
+        opt.view(0, B.MONA_VIEW_G_PREV)
+    assert ei.value.code == B.MONA_EUNSUPPORTED
+    dev_g = [g.to("cuda:0") for g in grads[0]]
+    with pytest.raises(B.MonaError) as ei:
+        opt.step(dev_g, hp)
+    assert ei.value.code == B.MONA_EINVAL
+    with pytest.raises(B.MonaError) as ei:
+        opt2.step(dev_g, hp, slots=slots)
+    assert ei.value.code == B.MONA_EINVAL
+    with pytest.raises(ValueError):
+        opt.step(dev_g, hp, slots=[s.t() for s in slots])
+    assert opt.step_count() == 4 and opt2.step_count() == 4
+
+
 def test_one_buffer_form_first_difference_flag_and_checkpoint():
     say("[case] one-buffer form: constant gradient with the first-difference flag; checkpoint")
     shapes = [(96, 160), (160, 96)]
