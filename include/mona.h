@@ -55,7 +55,7 @@ typedef enum mona_dtype { MONA_F32 = 0, MONA_BF16 = 1 } mona_dtype;
 typedef struct mona_matrix {
   void* w;            /* DEVICE: W_k in, W_{k+1} out                    */
   const void* g;      /* DEVICE: G_k                                    */
-  int32_t m, n;       /* >= 1; m * n < 2^31                             */
+  int32_t m, n;       /* 1 <= m, n <= 2^30; m * n < 2^31                */
   int32_t w_dtype;    /* mona_dtype                                     */
   int32_t g_dtype;    /* mona_dtype                                     */
 } mona_matrix;

@@ -92,6 +92,8 @@ int check_mats(const mona_matrix* mats, int32_t count, bool need_ptrs) {
   for (int i = 0; i < count; ++i) {
     const mona_matrix& q = mats[i];
     if (q.m < 1 || q.n < 1) return fail(MONA_EINVAL, "matrix %d: m and n must be >= 1 (got %d x %d)", i, q.m, q.n);
+    if (q.m > (1 << 30) || q.n > (1 << 30))   // sides are rounded up to tile multiples in 32-bit arithmetic
+      return fail(MONA_EINVAL, "matrix %d: m and n must each be at most 2^30 (got %d x %d)", i, q.m, q.n);
     if ((int64_t)q.m * q.n >= (int64_t)1 << 31)
       return fail(MONA_EINVAL, "matrix %d: m * n must be below 2^31 (got %d x %d)", i, q.m, q.n);
     if ((q.w_dtype != MONA_F32 && q.w_dtype != MONA_BF16) || (q.g_dtype != MONA_F32 && q.g_dtype != MONA_BF16))

@@ -158,7 +158,8 @@ __global__ __launch_bounds__(kEwThreads) void state_update_kernel(
           if constexpr (MODE == MODE_TWO_BUFFER) store4(gp + idx[b], vg[b]);   // G_{k-1} <- G_k
           if constexpr (MODE != MODE_MUON) store4(ac + idx[b], a);              // A_k, or C_{k+1}
           store4(mo + idx[b], mnew);
-          const int xo = (ldx == n) ? idx[b] : (idx[b] / n) * ldx + (idx[b] % n);
+          // the padded copy can exceed 2^31 elements although m * n does not: 64-bit offset
+          const int64_t xo = (ldx == n) ? (int64_t)idx[b] : (int64_t)(idx[b] / n) * ldx + (idx[b] % n);
           if (xf32) store4(xf + xo, mnew); else store4(xh + xo, mnew);
         }
       }
@@ -182,7 +183,7 @@ __global__ __launch_bounds__(kEwThreads) void state_update_kernel(
       }
       ss += mnew * mnew;
       mo[id] = mnew;
-      const int xo = (id / n) * ldx + (id % n);
+      const int64_t xo = (int64_t)(id / n) * ldx + (id % n);
       if (xf32) xf[xo] = mnew; else xh[xo] = (bf16_t)mnew;
     }
   }
@@ -247,7 +248,7 @@ __global__ __launch_bounds__(kEwThreads) void plain_update_kernel(
   const float keep = 1.0f - lr * wd, os = lr * gamma;
   for (int i = threadIdx.x; i < count; i += kEwThreads) {
     const int id = base + i;
-    const int xo = (id / ms.n) * ms.ldx + (id % ms.n);
+    const int64_t xo = (int64_t)(id / ms.n) * ms.ldx + (id % ms.n);
     // O = X_0 in the working precision of this matrix
     const float ov = xf32 ? sc.inv * xf[xo] : stored<bf16_t>(sc.inv * (float)xh[xo]);
     if (store_o) {

@@ -81,6 +81,11 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert rc == B.MONA_EINVAL and ">= 1" in msg
     rc, msg = rc_of(lib.mona_state_size, shapes((65536, 65536)), 1, None, C.byref(out))
     assert rc == B.MONA_EINVAL and "2^31" in msg
+    rc, msg = rc_of(lib.mona_state_size, shapes((2 ** 31 - 1, 1)), 1, None, C.byref(out))
+    assert rc == B.MONA_EINVAL and "2^30" in msg
+    # a long thin matrix below both limits is sized without overflow: 128 x 2^30 padded copies
+    assert lib.mona_state_size(shapes((1, 2 ** 30)), 1, None, C.byref(out)) == B.MONA_OK
+    assert out.value > 2 * 128 * 2 ** 30 * 2
     rc, _ = rc_of(lib.mona_state_size, shapes((4, 4), w=7), 1, None, C.byref(out))
     assert rc == B.MONA_EINVAL
     rc, _ = rc_of(lib.mona_state_size, shapes((4, 4)), 1, C.byref(B.mona_options(2, 0)), C.byref(out))
