@@ -454,6 +454,12 @@ struct BlockEpilogue {
 
   __device__ __forceinline__ void begin(int tmat, int row0, int col0, bool mir) {
     row_w0 = row0; col_w0 = col0; mirror = mir;
+    // The lane number is made opaque per tile: everything the epilogue derives from it (staging and
+    // global offsets) is then recomputed here, a few instructions, instead of being hoisted out of a
+    // persistent kernel's tile loop and held in registers across the K loop, where there are none to spare.
+    int l = threadIdx.x & 63;
+    asm volatile("" : "+v"(l));
+    lane = l;
     const int mi = a.members ? a.members[tmat] : tmat;
     post = 1.0f;
     if (a.post == POST_INV) post = a.scales[mi].inv;
@@ -961,7 +967,6 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
       });
     });
-    epi.begin(t.mat, t.ti * BM + wm * WM, t.tj * BN + wn * WN, a.symmetric && (t.tj * BN >= (t.ti + 1) * BM));
     // Stores of the previous epilogue may still be in flight and, unlike loads, may retire out of
     // order: counting "all but n" is only safe once they are gone, so drain everything here (the
     // loads of stages 0..2 were issued a whole epilogue ago).
@@ -988,6 +993,9 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
     step(IC<1>{}, kt + 1, IC<1>{}, IC<1>{}, IC<0>{}, IC<0>{});     // stage 3 done
     // the first epilogue bands are requested once no wait on the load counter is left, so that
     // they arrive while the last two steps are multiplied
+    // (the tile's output pointers and scales are looked up only now: nothing of the epilogue is held
+    // in registers across the K loop)
+    epi.begin(t.mat, t.ti * BM + wm * WM, t.tj * BN + wn * WN, a.symmetric && (t.tj * BN >= (t.ti + 1) * BM));
     epi.prefetch_first();
     step(IC<2>{}, kt + 2, IC<1>{}, IC<0>{}, IC<0>{}, IC<0>{});
     step(IC<3>{}, kt + 3, IC<0>{}, IC<0>{}, IC<0>{}, IC<0>{});
