@@ -704,14 +704,20 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 #define MONA_AS1 __attribute__((address_space(1)))
 #define MONA_AS3 __attribute__((address_space(3)))
 #ifdef MONA_TIMING
-// debug builds only: per-workgroup cycle stamps (kernel start, pipeline primed, main loop done, end)
-__device__ unsigned long long g_timing[4 * 65536];
+// debug builds only: per-workgroup cycle stamps of the last tile (0 kernel start, 1 K loop entered,
+// 2 K loop done, 3 epilogue done, 4 top of the round) and, in slot 5, the number of tiles walked
+__device__ unsigned long long g_timing[8 * 65536];
 #define MONA_STAMP(slot)                                                                     \
   do {                                                                                       \
-    if (threadIdx.x == 0 && blockIdx.x < 65536) g_timing[blockIdx.x * 4 + (slot)] = __builtin_readcyclecounter(); \
+    if (threadIdx.x == 0 && blockIdx.x < 65536) g_timing[blockIdx.x * 8 + (slot)] = __builtin_readcyclecounter(); \
+  } while (0)
+#define MONA_COUNT(slot, v)                                                                  \
+  do {                                                                                       \
+    if (threadIdx.x == 0 && blockIdx.x < 65536) g_timing[blockIdx.x * 8 + (slot)] = (unsigned long long)(v); \
   } while (0)
 #else
 #define MONA_STAMP(slot) do {} while (0)
+#define MONA_COUNT(slot, v) do {} while (0)
 #endif
 
 // A fragment as the LDS read instructions deliver it.  The registers are written when the data
@@ -961,6 +967,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
   issue(2, 2);
   for (int round = 0;; ++round) {
     // entry: chunks 0..2 of tile t are in flight (or landed) in stages 0..2; stage 3 is free
+    MONA_STAMP(4);
+    MONA_COUNT(5, round + 1);
     static_for<MI>([&](auto i) {
       static_for<NI>([&](auto j) {
 #pragma unroll
@@ -1134,21 +1142,22 @@ hipError_t launch_bf16(const GemmArgs& a, bool tp, bool tq, int grid, hipStream_
 static void dma_debug_report(const GemmArgs& a, bool transP, bool transQ, int grid, long long total) {
 #ifdef MONA_TIMING
   (void)hipDeviceSynchronize();
-  static unsigned long long host[4 * 65536];
+  static unsigned long long host[8 * 65536];
   const int nb = grid < 65536 ? grid : 65536;
-  (void)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_timing), sizeof(unsigned long long) * 4 * nb);
-  double s01 = 0, s12 = 0, s23 = 0;
+  (void)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_timing), sizeof(unsigned long long) * 8 * nb);
+  double s41 = 0, s12 = 0, s23 = 0, whole = 0, rounds = 0;
   int n = 0;
   for (int b = 0; b < nb && b < (int)total; ++b) {
-    const unsigned long long* q = host + 4 * b;
-    if (q[3] <= q[0]) continue;
-    s01 += (double)(q[1] - q[0]); s12 += (double)(q[2] - q[1]); s23 += (double)(q[3] - q[2]);
+    const unsigned long long* q = host + 8 * b;
+    if (q[3] <= q[0] || q[5] == 0) continue;
+    s41 += (double)(q[1] - q[4]); s12 += (double)(q[2] - q[1]); s23 += (double)(q[3] - q[2]);
+    whole += (double)(q[3] - q[0]); rounds += (double)q[5];
     ++n;
   }
   if (n)
-    fprintf(stderr, "[timing] tile %dx%d M %d N %d K %d sym %d tP %d tQ %d epi %d tiles %lld: prime %.0f  loop %.0f (%.1f/step)  epilogue %.0f\n",
-            a.tile_m, a.tile_n, a.M, a.N, a.K, a.symmetric, (int)transP, (int)transQ, a.epilogue, total, s01 / n, s12 / n,
-            s12 / n / (a.K / 32), s23 / n);
+    fprintf(stderr, "[timing] tile %dx%d M %d N %d K %d sym %d tP %d tQ %d epi %d tiles %lld: prime %.0f  loop %.0f (%.1f/step)  epilogue %.0f  per-tile %.0f rounds %.1f\n",
+            a.tile_m, a.tile_n, a.M, a.N, a.K, a.symmetric, (int)transP, (int)transQ, a.epilogue, total, s41 / n, s12 / n,
+            s12 / n / (a.K / 32), s23 / n, whole / rounds, rounds / n);
 #else
   (void)a; (void)transP; (void)transQ; (void)grid; (void)total;
 #endif
@@ -1179,12 +1188,13 @@ hipError_t launch_ns_gemm(const GemmArgs& a, int tile, bool transP, bool transQ,
 #define MONA_LAUNCH_DMA(TP_, TQ_, UPD_, E_)                                                                        \
   hipLaunchKernelGGL((ns_gemm_bf16_dma_kernel<256, 256, 2, 4, 4, 1, TP_, TQ_, UPD_, E_>), dim3(pgrid), dim3(512), 0, s, a)
     const bool upd = a.epilogue == EPI_UPDATE, has_e = a.E != nullptr;
-    // the plan uses: Gram (no E; both operands plain or both K-major), poly and apply (with E; P plain)
+    // the plan uses: Gram (no E; both operands row-major, or both K-major for a tall matrix); poly and the
+    // apply of a wide matrix (E, both operands K-major); the apply of a tall matrix and every apply that
+    // carries the update (E, P row-major, Q K-major)
     if (!transP && !transQ && !upd && !has_e) MONA_LAUNCH_DMA(false, false, false, false);
     else if (transP && transQ && !upd && !has_e) MONA_LAUNCH_DMA(true, true, false, false);
-    else if (!transP && !transQ && !upd && has_e) MONA_LAUNCH_DMA(false, false, false, true);
+    else if (transP && transQ && !upd && has_e) MONA_LAUNCH_DMA(true, true, false, true);
     else if (!transP && transQ && !upd && has_e) MONA_LAUNCH_DMA(false, true, false, true);
-    else if (!transP && !transQ && upd && has_e) MONA_LAUNCH_DMA(false, false, true, true);
     else if (!transP && transQ && upd && has_e) MONA_LAUNCH_DMA(false, true, true, true);
     else return hipErrorInvalidValue;
 #undef MONA_LAUNCH_DMA
