@@ -426,9 +426,12 @@ struct BlockEpilogue {
   const GemmArgs& a;
   int lane, row_w0, col_w0;
   bool mirror, skip_w, w_pref;
-  float post;
-  const bf16_t* __restrict__ E;
-  bf16_t* __restrict__ C;
+  float c_acc, c_e;              // out = c_acc * accumulator + c_e * E  (post-scale folded in)
+  // tile-relative addressing: wavefront-uniform 64-bit bases plus 32-bit lane offsets
+  const bf16_t* __restrict__ Et;
+  bf16_t* __restrict__ Ct;
+  bf16_t* __restrict__ Cm;       // base of the mirrored tile
+  uint32_t e_off, c_off;         // lane offsets (elements) of pass 0
   int wm_real, wn_real, w_is_bf16;
   void* wptr;
   u32x4 ev[HAS_E ? NPF : 1];
@@ -453,7 +456,8 @@ struct BlockEpilogue {
   }
 
   __device__ __forceinline__ void begin(int tmat, int row0, int col0, bool mir) {
-    row_w0 = row0; col_w0 = col0; mirror = mir;
+    row_w0 = row0; col_w0 = col0;
+    mirror = UPD ? false : mir;   // the launch that carries the update is an apply: never symmetric
     // The lane number is made opaque per tile: everything the epilogue derives from it (staging and
     // global offsets) is then recomputed here, a few instructions, instead of being hoisted out of a
     // persistent kernel's tile loop and held in registers across the K loop, where there are none to spare.
@@ -461,11 +465,18 @@ struct BlockEpilogue {
     asm volatile("" : "+v"(l));
     lane = l;
     const int mi = a.members ? a.members[tmat] : tmat;
-    post = 1.0f;
+    float post = 1.0f;
     if (a.post == POST_INV) post = a.scales[mi].inv;
     else if (a.post == POST_INV2) post = a.scales[mi].inv2;
-    E = HAS_E ? static_cast<const bf16_t*>(a.E) + (size_t)tmat * a.strideE : nullptr;
-    C = static_cast<bf16_t*>(a.C) + (size_t)tmat * a.strideC;
+    c_acc = post * a.alpha;
+    c_e = post * a.beta;
+    const int prow = lane >> 3, q = lane & 7;
+    Et = HAS_E ? static_cast<const bf16_t*>(a.E) + (size_t)tmat * a.strideE + (size_t)row0 * a.lde + col0 : nullptr;
+    bf16_t* const C = static_cast<bf16_t*>(a.C) + (size_t)tmat * a.strideC;
+    Ct = C + (size_t)row0 * a.ldc + col0;
+    Cm = C + (size_t)col0 * a.ldc + row0;
+    e_off = (uint32_t)(prow * a.lde + q * CH);
+    c_off = (uint32_t)(prow * a.ldc + q * CH);
     wm_real = wn_real = w_is_bf16 = 0;
     skip_w = true;
     wptr = nullptr;
@@ -484,9 +495,9 @@ struct BlockEpilogue {
   template <int P>
   __device__ __forceinline__ void prefetch() {
     constexpr int slot = P % NPF;
-    const int grow = row_w0 + pass_row(P) + (lane >> 3), gcol = col_w0 + (lane & 7) * CH;
-    if constexpr (HAS_E) ev[slot] = *reinterpret_cast<const u32x4*>(E + (size_t)grow * a.lde + gcol);
+    if constexpr (HAS_E) ev[slot] = *reinterpret_cast<const u32x4*>(Et + (e_off + (uint32_t)(pass_row(P) * a.lde)));
     if constexpr (UPD) {
+      const int grow = row_w0 + pass_row(P) + (lane >> 3), gcol = col_w0 + (lane & 7) * CH;
       if (w_pref && grow < wm_real && gcol + CH <= wn_real)
         wv[slot] = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(wptr) + (size_t)grow * wn_real + gcol);
     }
@@ -542,15 +553,15 @@ struct BlockEpilogue {
         if constexpr (HAS_E) {
           const bf16x8 e8 = __builtin_bit_cast(bf16x8, ev[slot]);
 #pragma unroll
-          for (int e = 0; e < CH; ++e) val[e] = post * (a.alpha * val[e] + a.beta * (float)e8[e]);
+          for (int e = 0; e < CH; ++e) val[e] = fmaf(c_acc, val[e], c_e * (float)e8[e]);
         } else {
 #pragma unroll
-          for (int e = 0; e < CH; ++e) val[e] = post * (a.alpha * val[e]);
+          for (int e = 0; e < CH; ++e) val[e] = c_acc * val[e];
         }
         bf16x8 ov;
 #pragma unroll
         for (int e = 0; e < CH; ++e) ov[e] = (bf16_t)val[e];
-        if (!UPD || a.store_out) *reinterpret_cast<bf16x8*>(C + (size_t)grow * a.ldc + gcol) = ov;
+        if (!UPD || a.store_out) *reinterpret_cast<bf16x8*>(Ct + (c_off + (uint32_t)(pass_row(p) * a.ldc))) = ov;
         // the rounded row, for the transposed store below: inside the fp32 row just read
         if (mirror) *reinterpret_cast<bf16x8*>(stage + r * 256 + (r & 3) * 32 + q * 16) = ov;
         if (UPD && !skip_w && grow < wm_real) {
@@ -591,7 +602,7 @@ struct BlockEpilogue {
         const int n = 16 * g + j16;
         static_for<4>([&](auto h) {
           const u32x4 tv = {lo[h].x, lo[h].y, hi[h].x, hi[h].y};
-          *reinterpret_cast<u32x4*>(C + (size_t)(col_w0 + n) * a.ldc + row_w0 + i * 32 + h * 8) = tv;
+          *reinterpret_cast<u32x4*>(Cm + ((uint32_t)(n * a.ldc) + (uint32_t)(i * 32 + h * 8))) = tv;
         });
       }
     });
@@ -916,12 +927,19 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
     static_assert(MI == 4 && NI == 2, "written for 4 x 2 blocks");
     wait_frags<pending>(fa[slot], fb[slot]);
   };
-  auto multiply = [&](auto slot) {
+  // fresh: the first product of a tile starts from a zero accumulator operand (an inline constant)
+  // instead of 128 registers cleared beforehand
+  auto multiply = [&](auto slot, auto fresh) {
     static_for<MI>([&](auto i) {
       static_for<NI>([&](auto j) {
         // operand roles swapped: the block is accumulated transposed (lane = output row), which is the
         // layout the epilogue stages with 16-byte LDS writes
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[slot][j].get(), fa[slot][i].get(), acc[i][j], 0, 0, 0);
+        if constexpr (fresh) {
+          const f32x16 zero = {};
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[slot][j].get(), fa[slot][i].get(), zero, 0, 0, 0);
+        } else {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[slot][j].get(), fa[slot][i].get(), acc[i][j], 0, 0, 0);
+        }
       });
     });
   };
@@ -933,17 +951,17 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
   //   SYNC:  wait for this wavefront's loads of stage u + 2 (all but LEFT newer loads done), then meet
   //          the other wavefronts: afterwards stage u + 2 is complete and stage u is free
   //   ISSUE: request chunk kt + 4 into stage u
-  auto step = [&](auto u, int kt, auto MORE, auto SYNC, auto LEFT, auto ISSUE) {
+  auto step = [&](auto u, int kt, auto MORE, auto SYNC, auto LEFT, auto ISSUE, auto FRESH) {
     fill(IC<1>{}, u, IC<1>{});
     arrive(IC<0>{}, IC<kPend>{});
-    multiply(IC<0>{});
+    multiply(IC<0>{}, FRESH);
     if constexpr (MORE) {
       fill(IC<0>{}, IC<(u + 1) & 3>{}, IC<0>{});
       arrive(IC<1>{}, IC<kPend>{});
     } else {
       arrive(IC<1>{}, IC<0>{});
     }
-    multiply(IC<1>{});
+    multiply(IC<1>{}, IC<0>{});
     if constexpr (SYNC) {
       MONA_WAIT_VM(LEFT);
       __builtin_amdgcn_s_barrier();     // bare barrier: a fence here would drain every load in flight
@@ -952,7 +970,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
   };
 
   static_assert(STAGES == 4, "the pipeline below is written for a ring of 4 stages");
-  typedef BlockEpilogue<MI, /*batch*/ (UPD ? 8 : 16), /*early*/ 2, UPD, HAS_E> Epi;
+  // (the launch that carries the update has no registers for an early request during the last K steps)
+  typedef BlockEpilogue<MI, /*batch*/ (UPD ? 8 : 16), /*early*/ (UPD ? 0 : 2), UPD, HAS_E> Epi;
   Epi epi(a);
   static_assert(NI == Epi::NI && (3 * STAGE_U * 16 + NW * Epi::kStageBytesPerWave) <= LDS_U * 16,
                 "epilogue staging: stage 3 and the LDS behind the ring");
@@ -969,12 +988,6 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
     // entry: chunks 0..2 of tile t are in flight (or landed) in stages 0..2; stage 3 is free
     MONA_STAMP(4);
     MONA_COUNT(5, round + 1);
-    static_for<MI>([&](auto i) {
-      static_for<NI>([&](auto j) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-      });
-    });
     // Stores of the previous epilogue may still be in flight and, unlike loads, may retire out of
     // order: counting "all but n" is only safe once they are gone, so drain everything here (the
     // loads of stages 0..2 were issued a whole epilogue ago).
@@ -986,27 +999,37 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
     int kt = 0;
     // first pass of the ring: chunk 3 is in flight alone, then the steady pattern sets in
     if (KT > 4) {
-      step(IC<0>{}, 0, IC<1>{}, IC<1>{}, IC<LPS>{}, IC<1>{});    // stage 2 landed long ago; LPS = chunk 3 may fly
-      step(IC<1>{}, 1, IC<1>{}, IC<1>{}, IC<LPS>{}, IC<1>{});    // chunk 3 done when only chunk 4's loads remain
-      step(IC<2>{}, 2, IC<1>{}, IC<1>{}, IC<LPS>{}, IC<1>{});
-      step(IC<3>{}, 3, IC<1>{}, IC<1>{}, IC<LPS>{}, IC<1>{});
+      step(IC<0>{}, 0, IC<1>{}, IC<1>{}, IC<LPS>{}, IC<1>{}, IC<1>{});   // stage 2 landed long ago; LPS = chunk 3 may fly
+      step(IC<1>{}, 1, IC<1>{}, IC<1>{}, IC<LPS>{}, IC<1>{}, IC<0>{});   // chunk 3 done when only chunk 4's loads remain
+      step(IC<2>{}, 2, IC<1>{}, IC<1>{}, IC<LPS>{}, IC<1>{}, IC<0>{});
+      step(IC<3>{}, 3, IC<1>{}, IC<1>{}, IC<LPS>{}, IC<1>{}, IC<0>{});
       kt = 4;
       for (; kt + 4 < KT; kt += 4) {
         // in flight at each SYNC: stages u + 2 and u + 3; stage u + 2 is done when LPS loads remain
-        static_for<4>([&](auto u) { step(u, kt + u, IC<1>{}, IC<1>{}, IC<LPS>{}, IC<1>{}); });
+        static_for<4>([&](auto u) { step(u, kt + u, IC<1>{}, IC<1>{}, IC<LPS>{}, IC<1>{}, IC<0>{}); });
       }
+    } else {
+      // a tile of four steps only: no first pass to start the accumulators from zero
+      static_for<MI>([&](auto i) {
+        static_for<NI>([&](auto j) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+        });
+      });
     }
     // last four steps: nothing left to request
-    step(IC<0>{}, kt + 0, IC<1>{}, IC<1>{}, IC<LPS>{}, IC<0>{});   // stage 2 done (its loads precede stage 3's)
-    step(IC<1>{}, kt + 1, IC<1>{}, IC<1>{}, IC<0>{}, IC<0>{});     // stage 3 done
+    step(IC<0>{}, kt + 0, IC<1>{}, IC<1>{}, IC<LPS>{}, IC<0>{}, IC<0>{});   // stage 2 done (its loads precede stage 3's)
+    step(IC<1>{}, kt + 1, IC<1>{}, IC<1>{}, IC<0>{}, IC<0>{}, IC<0>{});     // stage 3 done
     // the first epilogue bands are requested once no wait on the load counter is left, so that
     // they arrive while the last two steps are multiplied
     // (the tile's output pointers and scales are looked up only now: nothing of the epilogue is held
     // in registers across the K loop)
-    epi.begin(t.mat, t.ti * BM + wm * WM, t.tj * BN + wn * WN, a.symmetric && (t.tj * BN >= (t.ti + 1) * BM));
-    epi.prefetch_first();
-    step(IC<2>{}, kt + 2, IC<1>{}, IC<0>{}, IC<0>{}, IC<0>{});
-    step(IC<3>{}, kt + 3, IC<0>{}, IC<0>{}, IC<0>{}, IC<0>{});
+    if constexpr (!UPD) {
+      epi.begin(t.mat, t.ti * BM + wm * WM, t.tj * BN + wn * WN, a.symmetric && (t.tj * BN >= (t.ti + 1) * BM));
+      epi.prefetch_first();
+    }
+    step(IC<2>{}, kt + 2, IC<1>{}, IC<0>{}, IC<0>{}, IC<0>{}, IC<0>{});
+    step(IC<3>{}, kt + 3, IC<0>{}, IC<0>{}, IC<0>{}, IC<0>{}, IC<0>{});
     MONA_STAMP(2);
     // every wavefront is done with the operand stages: request the next tile's first chunks into
     // stages 0..2 now, so that they travel while this tile's epilogue runs out of stage 3
@@ -1019,6 +1042,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
       issue(1, 1);
       issue(2, 2);
     }
+    if constexpr (UPD) epi.begin(t.mat, t.ti * BM + wm * WM, t.tj * BN + wn * WN, false);
     epi.run(acc, stage_f);
     MONA_STAMP(3);
     if (!next.valid) break;
