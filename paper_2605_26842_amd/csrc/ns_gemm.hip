@@ -428,10 +428,10 @@ struct BlockEpilogue {
   bool mirror, skip_w, w_pref;
   float c_acc, c_e;              // out = c_acc * accumulator + c_e * E  (post-scale folded in)
   // tile-relative addressing: wavefront-uniform 64-bit bases plus 32-bit lane offsets
-  const bf16_t* __restrict__ Et;
-  bf16_t* __restrict__ Ct;
-  bf16_t* __restrict__ Cm;       // base of the mirrored tile
-  uint32_t e_off, c_off;         // lane offsets (elements) of pass 0
+  const char* __restrict__ Et;
+  char* __restrict__ Ct;
+  char* __restrict__ Cm;         // base of the mirrored tile
+  uint32_t e_off, c_off;         // lane offsets (bytes) of pass 0; a wavefront tile spans < 2^32 bytes
   int wm_real, wn_real, w_is_bf16;
   void* wptr;
   u32x4 ev[HAS_E ? NPF : 1];
@@ -455,6 +455,17 @@ struct BlockEpilogue {
     }
   }
 
+  // the same for one block row of the launch that carries the update: its block rows alternate between
+  // the two halves of the batch registers, and the next row is requested only after this wait, so
+  // nothing but this row's chunks (and the previous row's stores) is outstanding here
+  template <int H>
+  __device__ __forceinline__ void settle_half() {
+    static_assert(UPD && HAS_E && NPF == 8, "halves of a batch of 8 passes");
+    asm volatile("s_waitcnt vmcnt(0)"
+                 : "+v"(ev[4 * H]), "+v"(ev[4 * H + 1]), "+v"(ev[4 * H + 2]), "+v"(ev[4 * H + 3]),
+                   "+v"(wv[4 * H]), "+v"(wv[4 * H + 1]), "+v"(wv[4 * H + 2]), "+v"(wv[4 * H + 3]));
+  }
+
   __device__ __forceinline__ void begin(int tmat, int row0, int col0, bool mir) {
     row_w0 = row0; col_w0 = col0;
     mirror = UPD ? false : mir;   // the launch that carries the update is an apply: never symmetric
@@ -471,12 +482,14 @@ struct BlockEpilogue {
     c_acc = post * a.alpha;
     c_e = post * a.beta;
     const int prow = lane >> 3, q = lane & 7;
-    Et = HAS_E ? static_cast<const bf16_t*>(a.E) + (size_t)tmat * a.strideE + (size_t)row0 * a.lde + col0 : nullptr;
+    Et = HAS_E ? reinterpret_cast<const char*>(static_cast<const bf16_t*>(a.E) + (size_t)tmat * a.strideE +
+                                               (size_t)row0 * a.lde + col0)
+               : nullptr;
     bf16_t* const C = static_cast<bf16_t*>(a.C) + (size_t)tmat * a.strideC;
-    Ct = C + (size_t)row0 * a.ldc + col0;
-    Cm = C + (size_t)col0 * a.ldc + row0;
-    e_off = (uint32_t)(prow * a.lde + q * CH);
-    c_off = (uint32_t)(prow * a.ldc + q * CH);
+    Ct = reinterpret_cast<char*>(C + (size_t)row0 * a.ldc + col0);
+    Cm = reinterpret_cast<char*>(C + (size_t)col0 * a.ldc + row0);
+    e_off = 2u * (uint32_t)(prow * a.lde + q * CH);
+    c_off = 2u * (uint32_t)(prow * a.ldc + q * CH);
     wm_real = wn_real = w_is_bf16 = 0;
     skip_w = true;
     wptr = nullptr;
@@ -495,7 +508,7 @@ struct BlockEpilogue {
   template <int P>
   __device__ __forceinline__ void prefetch() {
     constexpr int slot = P % NPF;
-    if constexpr (HAS_E) ev[slot] = *reinterpret_cast<const u32x4*>(Et + (e_off + (uint32_t)(pass_row(P) * a.lde)));
+    if constexpr (HAS_E) ev[slot] = *reinterpret_cast<const u32x4*>(Et + (e_off + 2u * (uint32_t)(pass_row(P) * a.lde)));
     if constexpr (UPD) {
       const int grow = row_w0 + pass_row(P) + (lane >> 3), gcol = col_w0 + (lane & 7) * CH;
       if (w_pref && grow < wm_real && gcol + CH <= wn_real)
@@ -510,7 +523,11 @@ struct BlockEpilogue {
   // stage: kStageBytesPerWave bytes of LDS private to this wavefront, 256-byte aligned.
   __device__ __forceinline__ void run(f32x16 (&acc)[MI][NI], char* stage) {
     static_assert(NPRE <= NPF && PASSES % NPF == 0, "passes are fetched in batches of NPF");
-    static_for<NPF - NPRE>([&](auto p) { prefetch<NPRE + p>(); });
+    if constexpr (UPD) {
+      static_for<4>([&](auto p) { prefetch<p>(); });     // block row 0; row i + 1 follows while row i is worked on
+    } else {
+      static_for<NPF - NPRE>([&](auto p) { prefetch<NPRE + p>(); });
+    }
     const int srow = lane & 31, shalf = lane >> 5;       // staging writes: row and 4-column half
     const int prow = lane >> 3, q = lane & 7;            // passes: row inside the pass and 8-column chunk
     const uint32_t stage_addr = (uint32_t)(uintptr_t)(MONA_AS3_EPI const char*)stage;
@@ -518,15 +535,21 @@ struct BlockEpilogue {
       wave_sync();         // previous block row fully consumed
       static_for<NI>([&](auto j) {
         static_for<4>([&](auto vg) {
-          const int c = j * 8 + 2 * vg + shalf;
+          // 16-byte chunk c = 8 j + 2 vg + shalf of the row goes to slot (c >> 1) + 8 (c & 1), xor-ed with
+          // the row: eight consecutive rows of one chunk fall into eight different bank groups (the
+          // writes), and so do the eight even (or the eight odd) chunks of one row (the reads below)
+          const int slot_c = j * 4 + vg + 8 * shalf;
           f32x4 v = {acc[i][j][vg * 4 + 0], acc[i][j][vg * 4 + 1], acc[i][j][vg * 4 + 2], acc[i][j][vg * 4 + 3]};
-          *reinterpret_cast<f32x4*>(stage + srow * 256 + ((c ^ (srow & 15)) << 4)) = v;
+          *reinterpret_cast<f32x4*>(stage + srow * 256 + ((slot_c ^ (srow & 15)) << 4)) = v;
         });
       });
       wave_sync();
       // the batch this block row starts: request it (the first one was requested above) and wait once,
       // after the staging writes so that they overlap the latency
-      if constexpr ((i * 4) % NPF == 0) {
+      if constexpr (UPD) {
+        settle_half<i & 1>();
+        if constexpr (i + 1 < MI) static_for<4>([&](auto k) { prefetch<(i + 1) * 4 + k>(); });
+      } else if constexpr ((i * 4) % NPF == 0) {
         if constexpr (i > 0) static_for<NPF>([&](auto k) { prefetch<i * 4 + k>(); });
         settle();
       }
@@ -536,9 +559,11 @@ struct BlockEpilogue {
       f32x4 t[4][2];
       static_for<4>([&](auto pp) {
         const int r = pp * 8 + prow;
-        t[pp][0] = *reinterpret_cast<const f32x4*>(stage + r * 256 + (((2 * q) ^ (r & 15)) << 4));
-        t[pp][1] = *reinterpret_cast<const f32x4*>(stage + r * 256 + (((2 * q + 1) ^ (r & 15)) << 4));
+        t[pp][0] = *reinterpret_cast<const f32x4*>(stage + r * 256 + ((q ^ (r & 15)) << 4));         // chunk 2 q
+        t[pp][1] = *reinterpret_cast<const f32x4*>(stage + r * 256 + (((q + 8) ^ (r & 15)) << 4));   // chunk 2 q + 1
       });
+      // unit: the accumulator enters with factor 1 (every apply but the first), one operation less per element
+      auto passes = [&](auto unit) {
       static_for<4>([&](auto pp) {
         constexpr int p = i * 4 + pp;
         constexpr int slot = p % NPF;
@@ -553,7 +578,10 @@ struct BlockEpilogue {
         if constexpr (HAS_E) {
           const bf16x8 e8 = __builtin_bit_cast(bf16x8, ev[slot]);
 #pragma unroll
-          for (int e = 0; e < CH; ++e) val[e] = fmaf(c_acc, val[e], c_e * (float)e8[e]);
+          for (int e = 0; e < CH; ++e) {
+            if constexpr (unit) val[e] = fmaf(c_e, (float)e8[e], val[e]);
+            else val[e] = fmaf(c_acc, val[e], c_e * (float)e8[e]);
+          }
         } else {
 #pragma unroll
           for (int e = 0; e < CH; ++e) val[e] = c_acc * val[e];
@@ -561,7 +589,7 @@ struct BlockEpilogue {
         bf16x8 ov;
 #pragma unroll
         for (int e = 0; e < CH; ++e) ov[e] = (bf16_t)val[e];
-        if (!UPD || a.store_out) *reinterpret_cast<bf16x8*>(Ct + (c_off + (uint32_t)(pass_row(p) * a.ldc))) = ov;
+        if (!UPD || a.store_out) *reinterpret_cast<bf16x8*>(Ct + (c_off + 2u * (uint32_t)(pass_row(p) * a.ldc))) = ov;
         // the rounded row, for the transposed store below: inside the fp32 row just read
         if (mirror) *reinterpret_cast<bf16x8*>(stage + r * 256 + (r & 3) * 32 + q * 16) = ov;
         if (UPD && !skip_w && grow < wm_real) {
@@ -588,6 +616,8 @@ struct BlockEpilogue {
           }
         }
       });
+      };
+      if (HAS_E && c_acc == 1.0f) passes(IC<1>{}); else passes(IC<0>{});
       if (mirror) {
         // 16 lanes fetch a 4 (rows) x 16 (columns) block of the bf16 rows: lane j of the group points at
         // row j / 4, columns 4 (j % 4) .. + 3 and receives the 4 rows of column j.  Group g of the
@@ -602,7 +632,7 @@ struct BlockEpilogue {
         const int n = 16 * g + j16;
         static_for<4>([&](auto h) {
           const u32x4 tv = {lo[h].x, lo[h].y, hi[h].x, hi[h].y};
-          *reinterpret_cast<u32x4*>(Cm + ((uint32_t)(n * a.ldc) + (uint32_t)(i * 32 + h * 8))) = tv;
+          *reinterpret_cast<u32x4*>(Cm + 2u * ((uint32_t)(n * a.ldc) + (uint32_t)(i * 32 + h * 8))) = tv;
         });
       }
     });
