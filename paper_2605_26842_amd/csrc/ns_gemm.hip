@@ -812,11 +812,7 @@ __device__ __forceinline__ void lds_read_t(FragT& f, uint32_t addr) {
   asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.hi) : "v"(addr), "n"(OFF + PITCH4));
 }
 // s_waitcnt vmcnt(n), leaving the other counters alone (gfx9 encoding)
-#ifdef MONA_EXP_HALFDMA
-#define MONA_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | (((n) / 2) & 15) | ((((n) / 2) >> 4) << 14))
-#else
 #define MONA_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
-#endif
 
 template <int BM, int BN, int WGM, int WGN, int STAGES, int MIN_BLOCKS, bool TP, bool TQ, bool UPD, bool HAS_E>
 __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_kernel(const GemmArgs a) {
