@@ -219,6 +219,7 @@ constexpr int kDefaultLanes = 4;   // streams the shape groups of one step are s
 // 512 or 768 mid-sized groups (a bank of 64 experts of 1024 x 2048) lose 4 % by waiting for each other; at
 // 3072 the two expert groups of a 128-expert layer run side by side and lose 5 % to each other's L2 traffic.
 constexpr long long kBigLaunchTiles = 1536;
+constexpr long long kChipTiles = 256;      // one tile per CU
 
 struct LaunchRecord {
   int kind, group, iter, tile;
@@ -487,16 +488,28 @@ int mona_init_state(const mona_matrix* mats, int32_t count, const mona_options* 
     std::vector<std::pair<double, int>> order;
     std::vector<double> load(lanes, 0.0);
     st->lane_of_group.assign(L.groups.size(), 0);
+    std::vector<long long> fewest_of(L.groups.size(), 0);
+    bool any_big = false;
     for (size_t gi = 0; gi < L.groups.size(); ++gi) {
       const Group& g = L.groups[gi];
-      const double p = std::min(g.rows_pad, g.cols_pad), q = std::max(g.rows_pad, g.cols_pad);
-      const double work = (3.0 * p * p * q + p * p * p) * (double)g.members.size();
       long long fewest = -1;
       for (int kind = OP_GRAM; kind <= OP_APPLY; ++kind) {
         const long long t = launch_tiles(g, kind, pick_tile(g, kind, (int)g.members.size()), (int)g.members.size());
         if (fewest < 0 || t < fewest) fewest = t;
       }
-      if (fewest >= kBigLaunchTiles) load[0] += work;
+      fewest_of[gi] = fewest;
+      any_big = any_big || fewest >= kBigLaunchTiles;
+    }
+    for (size_t gi = 0; gi < L.groups.size(); ++gi) {
+      const Group& g = L.groups[gi];
+      const double p = std::min(g.rows_pad, g.cols_pad), q = std::max(g.rows_pad, g.cols_pad);
+      const double work = (3.0 * p * p * q + p * p * p) * (double)g.members.size();
+      // Beside a group that keeps the caller's stream, only groups too small to fill the chip by
+      // themselves go to the side streams (their launch latency hides behind the large group); a
+      // mid-sized group there gained 0.3 % at most (4 squares of 4096 beside 384 experts), and in a row
+      // the per-launch times of a profile add up to the phase time.
+      const bool in_row = fewest_of[gi] >= kBigLaunchTiles || (any_big && fewest_of[gi] >= kChipTiles);
+      if (in_row) load[0] += work;
       else order.emplace_back(-work, (int)gi);
     }
     std::sort(order.begin(), order.end());

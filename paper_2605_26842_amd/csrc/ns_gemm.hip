@@ -535,12 +535,9 @@ struct BlockEpilogue {
       wave_sync();         // previous block row fully consumed
       static_for<NI>([&](auto j) {
         static_for<4>([&](auto vg) {
-          // 16-byte chunk c = 8 j + 2 vg + shalf of the row goes to slot (c >> 1) + 8 (c & 1), xor-ed with
-          // the row: eight consecutive rows of one chunk fall into eight different bank groups (the
-          // writes), and so do the eight even (or the eight odd) chunks of one row (the reads below)
-          const int slot_c = j * 4 + vg + 8 * shalf;
+          const int c = j * 8 + 2 * vg + shalf;
           f32x4 v = {acc[i][j][vg * 4 + 0], acc[i][j][vg * 4 + 1], acc[i][j][vg * 4 + 2], acc[i][j][vg * 4 + 3]};
-          *reinterpret_cast<f32x4*>(stage + srow * 256 + ((slot_c ^ (srow & 15)) << 4)) = v;
+          *reinterpret_cast<f32x4*>(stage + srow * 256 + ((c ^ (srow & 15)) << 4)) = v;
         });
       });
       wave_sync();
@@ -559,8 +556,8 @@ struct BlockEpilogue {
       f32x4 t[4][2];
       static_for<4>([&](auto pp) {
         const int r = pp * 8 + prow;
-        t[pp][0] = *reinterpret_cast<const f32x4*>(stage + r * 256 + ((q ^ (r & 15)) << 4));         // chunk 2 q
-        t[pp][1] = *reinterpret_cast<const f32x4*>(stage + r * 256 + (((q + 8) ^ (r & 15)) << 4));   // chunk 2 q + 1
+        t[pp][0] = *reinterpret_cast<const f32x4*>(stage + r * 256 + (((2 * q) ^ (r & 15)) << 4));
+        t[pp][1] = *reinterpret_cast<const f32x4*>(stage + r * 256 + (((2 * q + 1) ^ (r & 15)) << 4));
       });
       // unit: the accumulator enters with factor 1 (every apply but the first), one operation less per element
       auto passes = [&](auto unit) {
