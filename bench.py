@@ -244,8 +244,6 @@ def main() -> int:
     # timed region: exactly --steps steps; phase times come from HIP events that mona_step
     # records on the stream it launches on
     opt.set_profiling(1)
-    phase = [0.0, 0.0, 0.0, 0.0]
-    n_phase = 0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -257,19 +255,9 @@ def main() -> int:
     eager_ms = ms_per_step
     if graph is not None:
         ms_per_step = graph_ms      # the phase split below still comes from eager, profiled steps
-    # events of the last timed step (the library keeps one set); then a few more profiled steps
-    # outside the timed region to average the phase split
-    times = opt.last_step_times()
-    phase = [phase[i] + times[i] for i in range(4)]
-    n_phase += 1
-    extra = min(args.steps, 5)
-    for _ in range(extra):
-        opt.step(ring[k % len(ring)], hpc)
-        k += 1
-        times = opt.last_step_times()
-        phase = [phase[i] + times[i] for i in range(4)]
-        n_phase += 1
-    ew_ms, ns_ms, upd_ms, step_ms_events = [p / n_phase for p in phase]
+    # phase split: the HIP events the library recorded, on the stream it launched on, around the
+    # phases of these very steps (it keeps the marks of the last 32 profiled steps)
+    (ew_ms, ns_ms, upd_ms, step_ms_events), n_phase = opt.mean_step_times()
 
     launches = None
     if args.per_launch:
@@ -341,7 +329,7 @@ def main() -> int:
             "traffic": traffic_ew,
         },
         "phases_ms": {"elementwise": ew_ms, "newton_schulz": ns_ms, "separate_update": upd_ms,
-                      "step_events": step_ms_events},
+                      "step_events": step_ms_events, "steps_averaged": n_phase},
         "ns_tflops_dense_equivalent": flops_dense / (ns_ms * 1e-3) / 1e12 if ns_ms > 0 else 0.0,
         "ns_tflops_issued": plan["ns_flops_issued"] / (ns_ms * 1e-3) / 1e12 if ns_ms > 0 else 0.0,
     }

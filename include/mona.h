@@ -211,6 +211,9 @@ int mona_state_status(mona_state* st, uint32_t* host_out, int32_t count, void* s
  *                         update (0 when fused into the last product), whole step. */
 int mona_set_profiling(mona_state* st, int32_t level /* 0 off, 1 phases, 2 every launch */);
 int mona_last_step_times(mona_state* st, float* ms_out);
+/* The same four figures averaged over the profiled steps since mona_set_profiling was last called (the
+ * last 32 of them if there were more); *steps_out says over how many.  Waits for those steps. */
+int mona_mean_step_times(mona_state* st, float* ms_out, int32_t* steps_out);
 
 /* With mona_set_profiling(st, 2) every Newton-Schulz product launch of a step is bracketed
  * by its own pair of events.  mona_last_step_launches waits for the step and fills up to

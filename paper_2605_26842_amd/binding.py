@@ -27,7 +27,7 @@ MONA_STATUS_ZERO_NORM, MONA_STATUS_NONFINITE = 0x1, 0x2
 EXPORTED = (
     "mona_state_size", "mona_init_state", "mona_step", "mona_step_streaming", "mona_free_state", "mona_state_view",
     "mona_state_export_size", "mona_state_export", "mona_state_import", "mona_state_step_count",
-    "mona_state_status", "mona_set_profiling", "mona_last_step_times", "mona_last_step_launches",
+    "mona_state_status", "mona_set_profiling", "mona_last_step_times", "mona_mean_step_times", "mona_last_step_launches",
     "mona_plan_info", "mona_last_error", "mona_version",
     "mona_adamw_state_size", "mona_adamw_init_state", "mona_adamw_step", "mona_adamw_free_state",
     "mona_adamw_state_view", "mona_adamw_state_export_size", "mona_adamw_state_export",
@@ -117,6 +117,7 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.mona_adamw_state_step_count.argtypes = [vp, P(i64)]
     lib.mona_set_profiling.argtypes = [vp, i32]
     lib.mona_last_step_times.argtypes = [vp, P(C.c_float)]
+    lib.mona_mean_step_times.argtypes = [vp, P(C.c_float), P(i32)]
     lib.mona_last_step_launches.argtypes = [vp, P(mona_launch_time), i32, P(i32)]
     lib.mona_plan_info.argtypes = [vp, i32, P(i64), P(C.c_double), P(C.c_double)]
     for name in EXPORTED:
@@ -305,6 +306,14 @@ class MonaOptimizer:
         out = (C.c_float * 4)()
         _check(self.lib.mona_last_step_times(self.state, out))
         return tuple(out)
+
+    def mean_step_times(self):
+        """The same four figures averaged over the steps profiled since set_profiling (at most the last 32),
+        and the number of steps averaged."""
+        out = (C.c_float * 4)()
+        n = C.c_int32(0)
+        _check(self.lib.mona_mean_step_times(self.state, out, C.byref(n)))
+        return tuple(out), n.value
 
     def last_step_launches(self):
         n = C.c_int32(0)

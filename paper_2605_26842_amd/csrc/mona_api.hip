@@ -214,6 +214,7 @@ void build_layout(const mona_matrix* mats, int count, const mona_options& opt, L
 }
 
 constexpr int kRing = 4;
+constexpr int kProfSets = 32;
 constexpr int kDefaultLanes = 4;   // streams the shape groups of one step are spread over
 // launches of at least this many tiles keep 256 CUs busy for six rounds or more.  Measured: with the limit at
 // 512 or 768 mid-sized groups (a bank of 64 experts of 1024 x 2048) lose 4 % by waiting for each other; at
@@ -253,7 +254,8 @@ struct mona_state {
   int device = 0;
   // profiling
   int profiling = 0;
-  hipEvent_t ev[4];
+  hipEvent_t ev[kProfSets][4];     // phase marks of the last kProfSets profiled steps, used in turn
+  int64_t prof_steps = 0;          // profiled steps since mona_set_profiling
   bool ev_valid = false;
   bool times_ready = false;
   bool fused_update = false;
@@ -451,7 +453,10 @@ int mona_init_state(const mona_matrix* mats, int32_t count, const mona_options* 
     for (int i = 0; i < kRing; ++i) {
       if (st->ring[i]) { (void)hipHostFree(st->ring[i]); (void)hipEventDestroy(st->ring_ev[i]); }
     }
-    if (st->ev_valid) for (auto& e : st->ev) (void)hipEventDestroy(e);
+    if (st->ev_valid)
+      for (auto& set : st->ev)
+        for (auto& e : set)
+          if (e) (void)hipEventDestroy(e);
     for (hipStream_t q : st->side) (void)hipStreamDestroy(q);
     for (hipEvent_t e : st->side_done) (void)hipEventDestroy(e);
     if (st->fork_ev) (void)hipEventDestroy(st->fork_ev);
@@ -476,8 +481,9 @@ int mona_init_state(const mona_matrix* mats, int32_t count, const mona_options* 
       return cleanup(fail(MONA_EHIP, "hipEventCreate: %s", hipGetErrorString(e)));
     }
   }
-  for (auto& e : st->ev) INIT_TRY(hipEventCreate(&e));
-  st->ev_valid = true;
+  for (auto& set : st->ev) for (auto& e : set) e = nullptr;
+  st->ev_valid = true;             // from here on cleanup() destroys the events created so far
+  for (auto& set : st->ev) for (auto& e : set) INIT_TRY(hipEventCreate(&e));
   {
     // Lanes.  A group whose every launch covers the chip many times over gains nothing from company
     // (two persistent kernels sharing the CUs only disturb each other's L2 reuse: measured slower), so
@@ -679,10 +685,11 @@ int step_impl(mona_state* st, const mona_matrix* mats, void* const* slots, int32
   const int nblocks = (int)L.blocks.size();
 
   const bool prof = st->profiling > 0;
+  hipEvent_t* const ev = st->ev[st->prof_steps % kProfSets];
   st->times_ready = false;
   st->records.clear();
   st->pool_used = 0;
-  if (prof) HIP_TRY(hipEventRecord(st->ev[0], s));
+  if (prof) HIP_TRY(hipEventRecord(ev[0], s));
 
   // Alg. 1: difference, acceleration EMA, accelerated gradient, momentum, roll; sum of squares
   const int use_prev = (hp->flags & MONA_FLAG_MUON_ONLY) ? 2 : !((hp->flags & MONA_FLAG_FIRST_DIFF_ZERO) && st->k == 0);
@@ -694,7 +701,7 @@ int step_impl(mona_state* st, const mona_matrix* mats, void* const* slots, int32
                               sbf, one, hp->momentum, hp->beta_a, hp->alpha, use_prev, s));
   if (L.one_buffer && !muon_only) st->last_beta_a = hp->beta_a;
   HIP_TRY(launch_norm_finalize(stat, partials, scales, count, hp->ns_eps, s));
-  if (prof) HIP_TRY(hipEventRecord(st->ev[1], s));
+  if (prof) HIP_TRY(hipEventRecord(ev[1], s));
 
   // Newton-Schulz (Eq. newton_schulz), T iterations of Gram / poly / apply per shape group
   const int T = hp->ns_steps;
@@ -741,15 +748,16 @@ int step_impl(mona_state* st, const mona_matrix* mats, void* const* slots, int32
       HIP_TRY(hipStreamWaitEvent(s, st->side_done[i], 0));
     }
   }
-  if (prof) HIP_TRY(hipEventRecord(st->ev[2], s));
+  if (prof) HIP_TRY(hipEventRecord(ev[2], s));
   if (T == 0) {
     // O = X_0, then Eq. muon_update
     HIP_TRY(launch_plain_update(stat, dyn, scales, blocks, nblocks, st->at<void*>(L.optr_off), hp->lr,
                                 hp->weight_decay, hp->gamma_coeff, (hp->flags & MONA_FLAG_KEEP_O) ? 1 : 0, s));
   }
   if (prof) {
-    HIP_TRY(hipEventRecord(st->ev[3], s));
+    HIP_TRY(hipEventRecord(ev[3], s));
     st->times_ready = true;
+    st->prof_steps += 1;
   }
   st->k += 1;
   return MONA_OK;
@@ -765,7 +773,10 @@ int mona_free_state(mona_state* st) {
     if (st->ring_used[i]) (void)hipEventSynchronize(st->ring_ev[i]);
     if (st->ring[i]) { (void)hipHostFree(st->ring[i]); (void)hipEventDestroy(st->ring_ev[i]); }
   }
-  if (st->ev_valid) for (auto& e : st->ev) (void)hipEventDestroy(e);
+  if (st->ev_valid)
+    for (auto& set : st->ev)
+      for (auto& e : set)
+        if (e) (void)hipEventDestroy(e);
   for (auto& pr : st->event_pool) { (void)hipEventDestroy(pr.first); (void)hipEventDestroy(pr.second); }
   for (hipStream_t q : st->side) { (void)hipStreamSynchronize(q); (void)hipStreamDestroy(q); }
   for (hipEvent_t e : st->side_done) (void)hipEventDestroy(e);
@@ -858,24 +869,46 @@ int mona_set_profiling(mona_state* st, int32_t on) {
   if (on < 0 || on > 2) return fail(MONA_EINVAL, "profiling level must be 0, 1 or 2");
   st->profiling = on;
   st->times_ready = false;
+  st->prof_steps = 0;
   return MONA_OK;
 }
 
 int mona_last_step_times(mona_state* st, float* ms_out) {
   if (!st || !ms_out) return fail(MONA_EINVAL, "state or ms_out is NULL");
   if (!st->times_ready) return fail(MONA_EINVAL, "no profiled step yet (call mona_set_profiling(st, 1) first)");
-  HIP_TRY(hipEventSynchronize(st->ev[3]));
-  HIP_TRY(hipEventElapsedTime(&ms_out[0], st->ev[0], st->ev[1]));
-  HIP_TRY(hipEventElapsedTime(&ms_out[1], st->ev[1], st->ev[2]));
-  HIP_TRY(hipEventElapsedTime(&ms_out[2], st->ev[2], st->ev[3]));
-  HIP_TRY(hipEventElapsedTime(&ms_out[3], st->ev[0], st->ev[3]));
+  hipEvent_t* const ev = st->ev[(st->prof_steps - 1) % kProfSets];
+  HIP_TRY(hipEventSynchronize(ev[3]));
+  HIP_TRY(hipEventElapsedTime(&ms_out[0], ev[0], ev[1]));
+  HIP_TRY(hipEventElapsedTime(&ms_out[1], ev[1], ev[2]));
+  HIP_TRY(hipEventElapsedTime(&ms_out[2], ev[2], ev[3]));
+  HIP_TRY(hipEventElapsedTime(&ms_out[3], ev[0], ev[3]));
+  return MONA_OK;
+}
+
+int mona_mean_step_times(mona_state* st, float* ms_out, int32_t* steps_out) {
+  if (!st || !ms_out || !steps_out) return fail(MONA_EINVAL, "state, ms_out or steps_out is NULL");
+  if (!st->times_ready) return fail(MONA_EINVAL, "no profiled step yet (call mona_set_profiling(st, 1) first)");
+  const int n = (int)std::min<int64_t>(st->prof_steps, kProfSets);
+  double sum[4] = {0.0, 0.0, 0.0, 0.0};
+  for (int b = 0; b < n; ++b) {
+    hipEvent_t* const ev = st->ev[(st->prof_steps - 1 - b) % kProfSets];
+    HIP_TRY(hipEventSynchronize(ev[3]));
+    const int from[4] = {0, 1, 2, 0}, to[4] = {1, 2, 3, 3};
+    for (int i = 0; i < 4; ++i) {
+      float ms = 0.0f;
+      HIP_TRY(hipEventElapsedTime(&ms, ev[from[i]], ev[to[i]]));
+      sum[i] += ms;
+    }
+  }
+  for (int i = 0; i < 4; ++i) ms_out[i] = (float)(sum[i] / n);
+  *steps_out = n;
   return MONA_OK;
 }
 
 int mona_last_step_launches(mona_state* st, mona_launch_time* out, int32_t max_records, int32_t* n_out) {
   if (!st || !n_out) return fail(MONA_EINVAL, "state or n_out is NULL");
   if (st->profiling < 2 || !st->times_ready) return fail(MONA_EINVAL, "no step profiled at level 2 yet");
-  HIP_TRY(hipEventSynchronize(st->ev[3]));
+  HIP_TRY(hipEventSynchronize(st->ev[(st->prof_steps - 1) % kProfSets][3]));
   const int n = (int)st->records.size();
   *n_out = n;
   if (!out) return MONA_OK;

@@ -531,7 +531,20 @@ def test_profiling_and_plan_reports():
     assert sorted({r["kind"] for r in recs}) == [0, 1, 2]
     assert abs(sum(r["flops"] for r in recs) - plan["ns_flops_issued"]) < 1e-6 * plan["ns_flops_issued"]
     assert all(r["ms"] > 0 for r in recs)
+    # the mean over the steps profiled since set_profiling: more steps than the library keeps marks for
+    opt.set_profiling(1)
+    with pytest.raises(B.MonaError):
+        opt.mean_step_times()
+    singles = []
+    for _ in range(40):
+        opt.step(grads, hp)
+        singles.append(opt.last_step_times())
+    mean, n = opt.mean_step_times()
+    assert n == 32
+    for i in range(4):
+        want = sum(x[i] for x in singles[-32:]) / 32
+        assert abs(mean[i] - want) <= 1e-3 * want + 1e-4
     opt.set_profiling(0)
     opt.step(grads, hp)
     torch.cuda.synchronize()
-    assert opt.step_count() == 2
+    assert opt.step_count() == 42
