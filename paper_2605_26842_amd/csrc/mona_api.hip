@@ -316,9 +316,9 @@ void fill_gemm(const mona_state* st, const Group& g, int kind, TileShape tile, i
   a.post = POST_NONE;
   // A_t and B_t are symmetric (bit for bit: mirrored tiles are copies, and a diagonal tile adds the same
   // products in the same order on both sides), so as operands they may be read K-major as well as
-  // row-major.  The large-tile kernel fetches a K-major operand in whole 512-byte rows instead of 64-byte
-  // pieces of 256 rows and runs 7-13 % faster per K step on it (measured), so it reads them that way;
-  // the small-tile kernels gain nothing from it.
+  // row-major.  The large-tile kernel fetches a K-major operand as 32 contiguous 512-byte rows instead of
+  // 64-byte pieces of 256 rows and runs 7-13 % faster per K step on it (measured), so it reads them that
+  // way; the small-tile kernels gain nothing from it.
   const bool symk = tile.bm == 256;
   if (kind == OP_GRAM) {
     a.P = X; a.Q = X; a.E = nullptr; a.C = S;
