@@ -10,14 +10,19 @@
 //
 //     out = post * (beta * E + alpha * P Q^T),     P: M x K,  Q: N x K
 //
-// over a batch of same-shape matrices.  An operand may be stored K-major (K x M); it is then
-// transposed in registers on its way into LDS, so the MFMA loop below always reads K-contiguous
-// rows.  All dimensions are padded by the host to multiples of the tile and the padding is kept
-// zero, so the main loop has no bounds checks.
+// over a batch of same-shape matrices.  An operand may be stored K-major (K x M).  All dimensions
+// are padded by the host to multiples of the tile and the padding is kept zero, so the main loops
+// have no bounds checks.  Symmetric products compute the block-upper-triangular tiles and mirror them.
 //
-// bf16 path: v_mfma_f32_32x32x16_bf16, fp32 accumulation, 256 threads = 4 wavefronts in a
-// 2 x 2 arrangement, block tile BM x BN (256 x 256 or 128 x 128), K step 64, LDS double buffer.
-// fp32 path: v_mfma_f32_32x32x2_f32, 128 x 128 tiles, K step 16.
+// Three kernels:
+//   ns_gemm_bf16_dma_kernel  the workhorse: persistent, 256 x 256 tile, 8 wavefronts of 128 x 64,
+//                            v_mfma_f32_32x32x16_bf16 with fp32 accumulation, operands sent straight from
+//                            global memory into a ring of four LDS stages of K = 32 (K-major tiles
+//                            are read from LDS with the transposing read), epilogue BlockEpilogue;
+//   ns_gemm_bf16_kernel      128 x 128 tile, 4 wavefronts, register-staged LDS double buffer of K = 64
+//                            (a K-major operand is transposed in registers on its way into LDS), for
+//                            launches too small to fill the chip with large tiles;
+//   ns_gemm_f32_kernel       v_mfma_f32_32x32x2_f32, 128 x 128 tile, K step 16, for fp32 products.
 #include "mona_internal.h"
 
 #include <cstdio>
