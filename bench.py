@@ -149,9 +149,10 @@ def main() -> int:
     ap.add_argument("--workload", default="moe_layer_h4096_e128")
     ap.add_argument("--ns-precision", type=int, default=0)
     ap.add_argument("--state-dtype", default="f32", choices=["f32", "bf16"])
-    ap.add_argument("--accel-form", default="two-buffer", choices=["two-buffer", "one-buffer"],
+    ap.add_argument("--accel-form", default="two-buffer", choices=["two-buffer", "one-buffer", "caller-slot"],
                     help="two-buffer: G_{k-1} and A stored as Alg. 1 writes it; one-buffer: no stored G_{k-1} "
-                         "(22 instead of 30 bytes per element in the elementwise pass)")
+                         "(22 instead of 30 bytes per element in the elementwise pass); caller-slot: G_{k-1} "
+                         "lives in arrays the caller keeps (Sec. 6.3's streaming form: same traffic, less state)")
     ap.add_argument("--g-dtype", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--grad-ring", type=int, default=2)
     ap.add_argument("--muon-only", action="store_true",
@@ -207,7 +208,11 @@ def main() -> int:
             streams = [wl.GradientStream(s, wl.matrix_seed(widx, i), dev) for i, s in enumerate(shapes)]
         ring.append([st.next().to(g_dtype) for st in streams])
     del streams
-    accel_form = B.MONA_ACCEL_ONE_BUFFER if args.accel_form == "one-buffer" else B.MONA_ACCEL_TWO_BUFFER
+    accel_form = {"two-buffer": B.MONA_ACCEL_TWO_BUFFER, "one-buffer": B.MONA_ACCEL_ONE_BUFFER,
+                  "caller-slot": B.MONA_ACCEL_CALLER_SLOT}[args.accel_form]
+    slots = None
+    if accel_form == B.MONA_ACCEL_CALLER_SLOT:
+        slots = [torch.zeros(s, dtype=state_dtype, device=dev) for s in shapes]
     opt = B.MonaOptimizer(weights, ns_precision=args.ns_precision, state_dtype=state_dtype, g_dtype=g_dtype,
                           accel_form=accel_form, max_streams=args.streams)
     hpc = B.make_hparams(hp)
@@ -223,17 +228,17 @@ def main() -> int:
 
     k = 0
     for _ in range(args.warmup):
-        opt.step(ring[k % len(ring)], hpc)
+        opt.step(ring[k % len(ring)], hpc, slots)
         k += 1
     torch.cuda.synchronize()
 
     graph = None
     if args.graph:
-        opt.step(ring[0], hpc)      # the pointer table now names ring[0]: the capture holds launches only
+        opt.step(ring[0], hpc, slots)      # the pointer table now names ring[0]: the capture holds launches only
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
-            opt.step(ring[0], hpc)
+            opt.step(ring[0], hpc, slots)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(args.steps):
@@ -247,7 +252,7 @@ def main() -> int:
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        opt.step(ring[k % len(ring)], hpc)
+        opt.step(ring[k % len(ring)], hpc, slots)
         k += 1
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -262,7 +267,7 @@ def main() -> int:
     launches = None
     if args.per_launch:
         opt.set_profiling(2)
-        opt.step(ring[k % len(ring)], hpc)
+        opt.step(ring[k % len(ring)], hpc, slots)
         k += 1
         launches = opt.last_step_launches()
         kinds = {0: "gram", 1: "poly", 2: "apply"}
