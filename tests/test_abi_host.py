@@ -70,6 +70,34 @@ def rc_of(fn, *args):
     return fn(*args), B.load_library().mona_last_error().decode()
 
 
+def test_state_size_properties_on_random_shape_lists():
+    """Properties of the arena layout that hold for any list of matrices: it holds at least the state and
+    the padded working copies, does not depend on the order of the matrices, and shrinks by exactly the
+    previous-gradient arrays when the caller keeps them or the one-buffer form is chosen."""
+    import random
+    rng = random.Random(20260527)
+    pad = lambda v: (v + 127) // 128 * 128
+    for _ in range(40):
+        k = rng.randint(1, 12)
+        base = [(rng.choice([1, 3, 64, 65, 100, 128, 256, 300, 512, 777, 1024]),
+                 rng.choice([1, 5, 64, 96, 128, 130, 256, 384, 640, 1000, 2048])) for _ in range(rng.randint(1, 4))]
+        mn = [rng.choice(base) for _ in range(k)]
+        two = B.mona_state_size(shapes(*mn), k)
+        elems = sum(m * n for m, n in mn)
+        work = sum(2 * pad(m) * pad(n) * (4 if min(m, n) <= 64 else 2) for m, n in mn)
+        assert two >= 12 * elems + work
+        assert two <= 12 * elems + 3 * work + 4096 * k + 65536       # X x 2, S, B (S, B <= X), tables, alignment
+        shuffled = mn[:]
+        rng.shuffle(shuffled)
+        assert B.mona_state_size(shapes(*shuffled), k) == two
+        one = B.mona_state_size(shapes(*mn), k, B.mona_options(0, B.MONA_F32, B.MONA_ACCEL_ONE_BUFFER))
+        kept = B.mona_state_size(shapes(*mn), k, B.mona_options(0, B.MONA_F32, B.MONA_ACCEL_CALLER_SLOT))
+        assert one == kept
+        aligned = sum((m * n * 4 + 255) // 256 * 256 for m, n in mn)
+        assert two - one == aligned
+        assert two % 256 == 0 and one % 256 == 0
+
+
 def test_bad_arguments_are_rejected_on_the_host():
     lib = B.load_library()
     out = C.c_size_t(0)
