@@ -445,7 +445,8 @@ def test_full_size_configs_sampled(name, sample, steps):
 def test_large_moe_layer_sampled():
     """configs[3]: 388 matrices (4 x 4096^2, 256 x 4096x1536, 128 x 1536x4096), one step at full
     size; oracle on one matrix of each expert shape (float64 Newton-Schulz on a 4096^2 matrix
-    takes too long on the host, the square class is covered at 2048^2 above)."""
+    takes too long on the host; the square class is covered at 2048^2 above and, at 4096^2, against
+    the SVD closed form below)."""
     name = "moe_layer_h4096_e128"
     say(f"[case] {name}")
     w = wl.WORKLOADS[name]
@@ -469,6 +470,56 @@ def test_large_moe_layer_sampled():
         fro2 = float((O.double() ** 2).sum())
         assert 0.45 * p <= fro2 <= 1.45 * p, (i, fro2, p)
         assert torch.isfinite(dev_w[i].float()).all()
+
+
+def test_square_4096_against_the_svd_closed_form():
+    """The largest short side of the BASELINE shapes, 4096 x 4096, is beyond a float64 Newton-Schulz on
+    the host.  What the iteration computes has a closed form, though: O = U diag(p^T(sigma_i / ||M||_F)) V^T
+    with p(s) = a s + b s^3 + c s^5 applied T times to the singular values of M (the oracle itself is pinned
+    to it on small matrices).  M_1 comes from the oracle's elementwise step on the host; the eigendecomposition
+    of M M^T is a library routine run in float64 (on the GPU, as a fast LAPACK); nothing expected here comes
+    from the HIP path."""
+    say("[case] 4096 x 4096 against the SVD closed form")
+    dev = "cuda:0"
+    shape = (4096, 4096)
+    # four of them, as in configs[3], so that the products run on the large-tile kernel
+    weights = [wl.draw_weight(shape, 7100 + i, torch.bfloat16, dev) for i in range(4)]
+    grads = [wl.GradientStream(shape, 7200 + i, dev).next() for i in range(4)]
+    hp = dataclasses.replace(wl.HParams(), flags=B.MONA_FLAG_KEEP_O)
+    opt = B.MonaOptimizer(weights)
+    opt.step(grads, hp)
+    torch.cuda.synchronize()
+    ohp = H.oracle_hp(hp)
+    for i in (0, 3):
+        o = orc.MonaOracle(shape)
+        o.elementwise(H.f64(grads[i]), ohp)
+        assert H.rel_max(H.f64(opt.momentum(i)), o.M) <= H.TOL_STATE
+        M = torch.from_numpy(o.M).to(dev)                       # float64
+        fro = torch.linalg.norm(M)
+        lam, U = torch.linalg.eigh(M @ M.T)
+        sigma = lam.clamp_min(0).sqrt() / fro                   # singular values of X_0
+        s = sigma.clone()
+        for _ in range(ohp.ns_steps):
+            s = ohp.ns_a * s + ohp.ns_b * s ** 3 + ohp.ns_c * s ** 5
+        # O = U diag(p^T(sigma)) V^T with V^T = diag(1 / (sigma fro)) U^T M
+        O_ref = (U * (s / (sigma * fro))) @ (U.T @ M)
+        O = opt.last_o(i).double()
+        err = float(torch.linalg.norm(O - O_ref) / torch.linalg.norm(O_ref))
+        say(f"[closed form] matrix {i}: sigma in [{float(sigma.min()):.3e}, {float(sigma.max()):.3e}], "
+            f"p^T(sigma) in [{float(s.min()):.4f}, {float(s.max()):.4f}], O rel Fro err {err:.3e}")
+        assert float(sigma.min()) > 1e-7                        # the closed form divides by sigma
+        assert err <= H.TOL_NS_BF16
+        # and the parameter moved by -eta (gamma O + lambda W) from the value it had
+        W0 = wl.draw_weight(shape, 7100 + i, torch.bfloat16, dev).double()
+        gamma = ohp.gamma_coeff * float(np.sqrt(max(shape)))
+        dW_ref = -ohp.lr * (gamma * O_ref + ohp.weight_decay * W0)
+        dW = weights[i].double() - W0
+        # the stored parameter is bf16: its rounding (half an ulp of values around 0.02) is part of dW
+        rounding = float(torch.linalg.norm((W0 + dW_ref).to(torch.bfloat16).double() - (W0 + dW_ref)) /
+                         torch.linalg.norm(dW_ref))
+        e_upd = float(torch.linalg.norm(dW - dW_ref) / torch.linalg.norm(dW_ref))
+        say(f"[closed form] matrix {i}: update rel Fro err {e_upd:.3e} (bf16 rounding of W alone {rounding:.3e})")
+        assert e_upd <= H.TOL_NS_BF16 + rounding
 
 
 def test_mixed_large_and_small_groups_on_several_streams():
