@@ -472,6 +472,43 @@ def test_large_moe_layer_sampled():
         assert torch.isfinite(dev_w[i].float()).all()
 
 
+def test_four_layer_stack_sampled():
+    """The resident part of configs[4] (4 of its 24 layers: 1560 matrices, 9.95 G elements, about 190 GB
+    with parameters, gradients, state and working copies), one step at full size: the oracle on one
+    matrix of each expert shape and of each router/projection shape, from different layers."""
+    name = "moe_stack_l4"
+    say(f"[case] {name}")
+    w = wl.WORKLOADS[name]
+    idx = list(wl.WORKLOADS).index(name)
+    dev = "cuda:0"
+    free, _ = torch.cuda.mem_get_info()
+    if free < 230 * 2 ** 30:
+        pytest.skip(f"needs about 200 GB of free device memory, {free / 2 ** 30:.0f} GB are free")
+    shapes = w.shapes()
+    per_layer = len(shapes) // 4
+    # layer 3: a tall expert; layer 2: a wide expert; layer 1: the 4096 x 512 matrix; layer 0: the 512 x 4096 one
+    sample = [3 * per_layer + 4 + 100, 2 * per_layer + 4 + 256 + 77, per_layer + 388, 389]
+    assert [shapes[i] for i in sample] == [(4096, 1536), (1536, 4096), (4096, 512), (512, 4096)]
+    weights = [wl.draw_weight(s, wl.matrix_seed(idx, i), w.w_dtype, dev) for i, s in enumerate(shapes)]
+    grads = [[wl.GradientStream(s, wl.matrix_seed(idx, i), dev).next() for i, s in enumerate(shapes)]]
+    say("[case] inputs resident")
+    hp = wl.HParams()
+    w_cpu = [x.cpu() if i in sample else x for i, x in enumerate(weights)]
+    opt, dev_w, hist = H.run_gpu(weights, grads, hp, 0, watch=sample)
+    say("[case] step done")
+    worst = H.check_history(w_cpu, grads, hp, hist, sample, H.TOL_NS_BF16, label=name)
+    say("[worst]", worst)
+    assert opt.status() == [0] * len(shapes)
+    for i in (0, per_layer - 1, 2 * per_layer + 5, len(shapes) - 1):
+        O = opt.last_o(i).float()
+        p = min(shapes[i])
+        fro2 = float((O.double() ** 2).sum())
+        assert 0.45 * p <= fro2 <= 1.45 * p, (i, fro2, p)
+        assert torch.isfinite(dev_w[i].float()).all()
+    del opt, dev_w, hist, weights, grads
+    torch.cuda.empty_cache()
+
+
 def test_square_4096_against_the_svd_closed_form():
     """The largest short side of the BASELINE shapes, 4096 x 4096, is beyond a float64 Newton-Schulz on
     the host.  What the iteration computes has a closed form, though: O = U diag(p^T(sigma_i / ||M||_F)) V^T
