@@ -481,8 +481,11 @@ def test_four_layer_stack_sampled():
     w = wl.WORKLOADS[name]
     idx = list(wl.WORKLOADS).index(name)
     dev = "cuda:0"
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()          # hand the blocks earlier tests left in torch's cache back first
     free, _ = torch.cuda.mem_get_info()
-    if free < 230 * 2 ** 30:
+    if free < 210 * 2 ** 30:
         pytest.skip(f"needs about 200 GB of free device memory, {free / 2 ** 30:.0f} GB are free")
     shapes = w.shapes()
     per_layer = len(shapes) // 4
