@@ -35,7 +35,12 @@ printed numeric example in the paper: "parity unpinned" beyond those pins.
 
 MONA-Lite (Sec. 6.3, low-precision state): `state_dtype="bf16"` rounds the
 stored G_{k-1} and A_k to bfloat16 (round-to-nearest-even) after each step's
-arithmetic, the arithmetic itself unchanged.
+arithmetic, the arithmetic itself unchanged: G~_k and M_k use the unrounded
+A_k of the same step, the next step's D and EMA read the rounded values back,
+and M stays full precision.  The paper prints no numbers for this variant;
+the reading is fixed by a two-step example worked by hand in exact fractions
+(tests/golden/bf16_state_worked_example.txt), which a rounding placed
+anywhere else fails.
 
 One-buffer form of the acceleration term (`accel_form="one_buffer"`; the
 goal of Sec. 6.3's streaming variant, no stored G_{k-1}, reached by algebra

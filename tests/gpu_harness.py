@@ -135,16 +135,24 @@ def check_history(weights, grads_per_step, hp, history, watch, ns_tol, state_tol
             dW = s.W - s.W_before
             e = rel_fro(dW, dW_ref)
             worst["upd"] = max(worst["upd"], e)
-            extra = 0.0
             if bf16_param:
-                # storing the parameter in bf16 adds one rounding of W_{k+1}; measure its size
-                extra = np.linalg.norm(orc.round_to_bf16(want) - want) / max(np.linalg.norm(dW_ref), 1e-300)
-                # and the update arithmetic itself is exact given the GPU's own O: at most one
+                # the same figure with the rounding of the stored parameter made part of the reference
+                # (reported, and bounded like the other one)
+                e_r = rel_fro(dW, orc.round_to_bf16(want) - s.W_before)
+                worst["upd_vs_rounded_ref"] = max(worst.get("upd_vs_rounded_ref", 0.0), e_r)
+                # the update arithmetic itself is exact given the GPU's own O: at most one
                 # bf16 ulp away from the float64 formula on a vanishing fraction of elements
                 mine = expected_update(s.W_before, s.O, hp, True)
                 diff = np.abs(mine - s.W)
                 ulp = np.maximum(np.abs(mine), 2.0 ** -126) * 2.0 ** -7
                 assert (diff <= ulp).all(), f"{tag}: bf16 parameter more than one ulp off"
                 assert (diff > 0).mean() <= 2e-3, f"{tag}: {(diff > 0).mean():.2e} of parameters mis-rounded"
-            assert e <= ns_tol + extra, f"{tag}: update rel Frobenius err {e:.3e} > {ns_tol} + {extra:.2e}"
+                if ns_tol < 1e-3:
+                    # fp32-class products with a bf16 parameter: the rounding of W_{k+1} (about 1e-2 of
+                    # the update at these magnitudes) is far above the 1e-4 bound, which therefore applies
+                    # to O (above) and to the arithmetic given O (the one-ulp check just made)
+                    continue
+                assert e_r <= ns_tol, f"{tag}: update rel Frobenius err vs the rounded reference {e_r:.3e} > {ns_tol}"
+            # no allowance for the parameter's own rounding: the bound is on the update as stored
+            assert e <= ns_tol, f"{tag}: update rel Frobenius err {e:.3e} > {ns_tol}"
     return worst

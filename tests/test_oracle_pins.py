@@ -276,6 +276,16 @@ def test_newton_schulz_rank_one_and_scaled_identity():
         ref[:, :p] = -val * np.eye(p)
         np.testing.assert_allclose(O, ref, rtol=0, atol=1e-11)
     assert scalar_poly_iter(1 / 16.0, 5, a, b, c) == pytest.approx(1.070524447724669, rel=1e-12)
+    # the short sides of the benchmark shapes: p^5(1 / sqrt(p)) for p = 1024 and p = 4096, and the oracle
+    # itself on kappa [I_p 0] at p = 1024 (one 1024 x 1024 Gram matrix per iteration: well under a second)
+    assert scalar_poly_iter(1 / 32.0, 5, a, b, c) == pytest.approx(1.1329236117054717, rel=1e-12)
+    assert scalar_poly_iter(1 / 64.0, 5, a, b, c) == pytest.approx(0.9025257529666177, rel=1e-12)
+    M = np.zeros((1024, 1056))
+    M[:, :1024] = 0.75 * np.eye(1024)
+    O = newton_schulz(M, 5)
+    ref = np.zeros_like(M)
+    ref[:, :1024] = 1.1329236117054717 * np.eye(1024)
+    np.testing.assert_allclose(O, ref, rtol=0, atol=1e-11)
 
 
 @pytest.mark.parametrize("shape", [(40, 12), (12, 40), (25, 25), (33, 1)])
@@ -400,6 +410,28 @@ def test_run_oracle_history_and_bf16_state_variant():
     assert np.array_equal(Wb[1], Wf[1])
 
 
+def test_bf16_state_worked_example():
+    """Where the bf16 rounding of the MONA-Lite state falls (Sec. 6.3): a two-step example worked by
+    hand in exact fractions, stored under tests/golden with its derivation."""
+    rows = []
+    with open(os.path.join(os.path.dirname(__file__), "golden", "bf16_state_worked_example.txt")) as f:
+        for line in f:
+            line = line.split("#", 1)[0].split()
+            if line:
+                rows.append([int(x) for x in line])
+    assert len(rows) == 4
+    hp = OracleHParams(beta_a=0.5, alpha=1.0, momentum=0.5)
+    o = MonaOracle((1, 2), state_dtype="bf16")
+    for step in (1, 2):
+        r = sorted((x for x in rows if x[0] == step), key=lambda x: x[1])
+        frac = lambda i: np.array([[r[0][i] / r[0][i + 1], r[1][i] / r[1][i + 1]]])   # dyadic: exact in float64
+        M = o.elementwise(frac(2), hp)
+        assert np.array_equal(M, frac(4)), (step, M)
+        assert np.array_equal(o.G_tilde, frac(6)), (step, o.G_tilde)
+        assert np.array_equal(o.A, frac(8)), (step, o.A)
+        assert np.array_equal(o.G_prev, frac(10)), (step, o.G_prev)
+
+
 # ----------------------------------------------------------------------------
 # one-buffer form of the acceleration term: same A_k, G~_k, M_k as Alg. 1
 # ----------------------------------------------------------------------------
@@ -461,6 +493,7 @@ def _pins_pass():
         test_update_special_cases()
         test_full_step_composes_the_parts()
         test_alpha_zero_is_plain_muon((16, 24))
+        test_bf16_state_worked_example()
     except AssertionError:
         return False
     return True
@@ -550,8 +583,42 @@ def test_planted_mistakes_are_caught(monkeypatch):
         self.k += 1
         return self.M
 
+    def elem_bf16_rounds_a_before_use(self, G, hp):
+        if self.state_dtype != "bf16" or self.accel_form != "two_buffer":
+            return real_elem(self, G, hp)
+        G = np.asarray(G, dtype=np.float64)
+        D = G - self.G_prev
+        self.A = orc.round_to_bf16(hp.beta_a * self.A + (1 - hp.beta_a) * D)   # rounded before it feeds G~
+        self.G_tilde = G + hp.alpha * self.A
+        self.M = hp.momentum * self.M + self.G_tilde
+        self.G_prev = orc.round_to_bf16(G)
+        self.k += 1
+        return self.M
+
+    def elem_bf16_diff_against_unrounded_gradient(self, G, hp):
+        if self.state_dtype != "bf16" or self.accel_form != "two_buffer":
+            return real_elem(self, G, hp)
+        G = np.asarray(G, dtype=np.float64)
+        exact_prev = getattr(self, "_exact_prev", np.zeros_like(G))
+        D = G - exact_prev                             # as if G_{k-1} had been kept in full precision
+        self.A = hp.beta_a * self.A + (1 - hp.beta_a) * D
+        self.G_tilde = G + hp.alpha * self.A
+        self.M = hp.momentum * self.M + self.G_tilde
+        self._exact_prev = G.copy()
+        self.A = orc.round_to_bf16(self.A)
+        self.G_prev = orc.round_to_bf16(G)
+        self.k += 1
+        return self.M
+
+    def elem_bf16_rounds_momentum_too(self, G, hp):
+        M = real_elem(self, G, hp)
+        if self.state_dtype == "bf16":
+            self.M = orc.round_to_bf16(self.M)         # M stays full precision in MONA-Lite
+        return self.M
+
     for bad in (elem_no_roll, elem_momentum_on_raw_gradient, elem_ema_damped_momentum, elem_diff_sign,
-                elem_one_buffer_carry_without_square):
+                elem_one_buffer_carry_without_square, elem_bf16_rounds_a_before_use,
+                elem_bf16_diff_against_unrounded_gradient, elem_bf16_rounds_momentum_too):
         monkeypatch.setattr(MonaOracle, "elementwise", bad)
         assert not _pins_pass(), bad.__name__
     monkeypatch.setattr(MonaOracle, "elementwise", real_elem)
