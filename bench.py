@@ -163,6 +163,9 @@ def main() -> int:
                     help="also run one plain 1 GiB elementwise copy (negation; a reference kernel of known traffic for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--ns-steps", type=int, default=5, help="Newton-Schulz iterations T (the paper's 5)")
+    ap.add_argument("--ns-schedule", default="auto", choices=["auto", "literal", "fused"],
+                    help="layout of the Newton-Schulz iterations as products: literal = Gram, poly, apply per "
+                         "iteration; fused = chunks of iterations advanced on the p x p side; auto = the library's choice")
     ap.add_argument("--streams", type=int, default=0,
                     help="streams the shape groups' launch chains are spread over (0 = library default, 1 = one)")
     ap.add_argument("--graph", action="store_true",
@@ -214,7 +217,8 @@ def main() -> int:
     if accel_form == B.MONA_ACCEL_CALLER_SLOT:
         slots = [torch.zeros(s, dtype=state_dtype, device=dev) for s in shapes]
     opt = B.MonaOptimizer(weights, ns_precision=args.ns_precision, state_dtype=state_dtype, g_dtype=g_dtype,
-                          accel_form=accel_form, max_streams=args.streams)
+                          accel_form=accel_form, max_streams=args.streams,
+                          ns_schedule={"auto": 0, "literal": 1, "fused": 2}[args.ns_schedule])
     hpc = B.make_hparams(hp)
     plan = opt.plan_info(hp.ns_steps)
     torch.cuda.synchronize()
@@ -270,7 +274,7 @@ def main() -> int:
         opt.step(ring[k % len(ring)], hpc, slots)
         k += 1
         launches = opt.last_step_launches()
-        kinds = {0: "gram", 1: "poly", 2: "apply"}
+        kinds = {0: "gram", 1: "poly", 2: "apply", 3: "sym"}
         for r in launches:
             tf = r["flops"] / (r["ms"] * 1e-3) / 1e12 if r["ms"] > 0 else 0.0
             print(f"[launch] {kinds[r['kind']]:5s} {r['m']}x{r['n']} x{r['count']} iter {r['iter']} tile {r['tile']}: "
@@ -316,6 +320,7 @@ def main() -> int:
             "state_dtype": args.state_dtype, "accel_form": args.accel_form, "ns_steps": hp.ns_steps, "ns_precision": args.ns_precision,
             "grad_ring": len(ring), "optimizer": "muon" if args.muon_only else "mona",
             "launch": "hip graph replay" if graph is not None else "eager", "streams": args.streams,
+            "ns_schedule": args.ns_schedule,
         },
         "roofline": {
             "kernel": "ns_gemm (grouped Newton-Schulz products, %d launches/step)" % plan["ns_launches"],

@@ -21,7 +21,8 @@
  * Conventions
  *   - plain C ABI; every pointer argument says whether it is HOST or DEVICE memory;
  *   - every function returns MONA_OK (0) or a negative mona_status and never throws;
- *     mona_last_error() gives a thread-local description of the last failure;
+ *     mona_last_error() gives a thread-local description of the last failure (a successful
+ *     mona_step may leave a warning there: see mona_step);
  *   - nothing here synchronises the stream unless stated; work is enqueued on the
  *     stream the caller passes (a hipStream_t cast to void*, NULL = the null stream);
  *   - the library allocates no device memory for state or workspace: the caller hands
@@ -105,8 +106,23 @@ typedef struct mona_options {
                            chains run on up to this many streams (the caller's plus side streams the
                            state owns, forked after the elementwise pass and joined before mona_step
                            returns, all at default priority).  0 = default (4), 1 = caller's stream only */
-  int32_t reserved[4];  /* must be 0 */
+  int32_t ns_schedule;  /* how the T iterations of Eq. newton_schulz are laid out as matrix products (the
+                           polynomial of X_0 they compute is the same; rounding differs):
+                           MONA_NS_SCHEDULE_LITERAL (1): per iteration S = X X^T, B = b S + c S S, X <- a X + B X;
+                           MONA_NS_SCHEDULE_FUSED (2): iterations in chunks of three, then two.  With
+                             Q_t = a I + b S_t + c S_t^2 an iteration is X_{t+1} = Q_t X_t and S_{t+1} = S_t Q_t^2,
+                             so a chunk forms S once, advances it on the p x p side and applies the product of its
+                             Q_t to X once: fewer flop whenever the long side exceeds the short one;
+                           MONA_NS_SCHEDULE_AUTO (0): fused for bf16 groups whose long side q is at least 1.5
+                             times the short side p and for which 1 / sqrt(p) + 1 / sqrt(q) <= 0.0438 (e.g.
+                             1536 x 4096, 2048 x 8192: there the fused form measured as accurate as the literal
+                             one or better), literal otherwise                                          */
+  int32_t reserved[3];  /* must be 0 */
 } mona_options;
+
+#define MONA_NS_SCHEDULE_AUTO 0
+#define MONA_NS_SCHEDULE_LITERAL 1
+#define MONA_NS_SCHEDULE_FUSED 2
 
 #define MONA_ACCEL_TWO_BUFFER 0
 #define MONA_ACCEL_ONE_BUFFER 1
@@ -146,7 +162,11 @@ int mona_init_state(const mona_matrix* mats, int32_t count, const mona_options* 
  * and may be recorded into a HIP graph on a capturing stream.
  * The hyper-parameters are baked into the recorded launches, and the host-side step
  * counter counts calls, not replays (it only matters for MONA_FLAG_FIRST_DIFF_ZERO at
- * the first step). */
+ * the first step).
+ * The convergence theorem (Theorem 1) assumes |alpha| < 1 / (1 - beta_a).  A step outside that range
+ * is taken all the same and returns MONA_OK; mona_last_error() then holds a warning that says so.
+ * If a HIP call fails after the first kernel of a step was enqueued, the state arrays are half updated:
+ * the call returns MONA_EHIP and every later step on this state does, until a checkpoint is imported. */
 int mona_step(mona_state* st, const mona_matrix* mats, int32_t count,
               const mona_hparams* hp, void* stream);
 
@@ -203,6 +223,9 @@ int mona_state_step_count(mona_state* st, int64_t* k_out);
  * bit 1: ||M||_F not finite (the matrix's W was left unchanged). */
 #define MONA_STATUS_ZERO_NORM 0x1u
 #define MONA_STATUS_NONFINITE 0x2u
+/* bit 2 (informative): ||M||_F lay outside [2^-40, 2^40], so the working copy of M was rescaled by a power
+ * of two before the products (the result is unaffected: Sec. 3.2's X_0 = M / ||M||_F is scale-free). */
+#define MONA_STATUS_RESCALED 0x4u
 int mona_state_status(mona_state* st, uint32_t* host_out, int32_t count, void* stream);
 
 /* Elapsed GPU time of the phases of the last mona_step, from HIP events recorded on the
@@ -218,7 +241,8 @@ int mona_mean_step_times(mona_state* st, float* ms_out, int32_t* steps_out);
 /* With mona_set_profiling(st, 2) every Newton-Schulz product launch of a step is bracketed
  * by its own pair of events.  mona_last_step_launches waits for the step and fills up to
  * max_records entries (out may be NULL to query the count).
- *   kind: 0 = Gram (X X^T), 1 = poly (b S + c S S), 2 = apply (a X + B X)
+ *   kind: 0 = Gram (X X^T), 1 = poly (b S + c S S [+ a I]), 2 = apply (a X + B X, or R X),
+ *         3 = product of two commuting symmetric p x p matrices (fused schedule)
  *   tile:  block tile of the kernel, rows * 1000 + columns (e.g. 256128)
  *   flops: MFMA flop the launch issues (tiles x 2 x rows x columns x K), padding included */
 typedef struct mona_launch_time {

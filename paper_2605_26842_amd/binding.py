@@ -22,10 +22,12 @@ MONA_F32, MONA_BF16 = 0, 1
 MONA_FLAG_FIRST_DIFF_ZERO, MONA_FLAG_KEEP_O, MONA_FLAG_MUON_ONLY = 0x1, 0x2, 0x4
 MONA_VIEW_G_PREV, MONA_VIEW_A, MONA_VIEW_M, MONA_VIEW_NORM, MONA_VIEW_O, MONA_VIEW_C = 0, 1, 2, 3, 4, 5
 MONA_ACCEL_TWO_BUFFER, MONA_ACCEL_ONE_BUFFER, MONA_ACCEL_CALLER_SLOT = 0, 1, 2
-MONA_STATUS_ZERO_NORM, MONA_STATUS_NONFINITE = 0x1, 0x2
+MONA_STATUS_ZERO_NORM, MONA_STATUS_NONFINITE, MONA_STATUS_RESCALED = 0x1, 0x2, 0x4
+MONA_NS_SCHEDULE_AUTO, MONA_NS_SCHEDULE_LITERAL, MONA_NS_SCHEDULE_FUSED = 0, 1, 2
 
 EXPORTED = (
-    "mona_state_size", "mona_init_state", "mona_step", "mona_step_streaming", "mona_free_state", "mona_state_view",
+    "mona_state_size", "mona_init_state", "mona_step", "mona_step_streaming", "mona_free_state",
+    "mona_state_view",
     "mona_state_export_size", "mona_state_export", "mona_state_import", "mona_state_step_count",
     "mona_state_status", "mona_set_profiling", "mona_last_step_times", "mona_mean_step_times", "mona_last_step_launches",
     "mona_plan_info", "mona_last_error", "mona_version",
@@ -59,7 +61,7 @@ class mona_hparams(C.Structure):
 
 class mona_options(C.Structure):
     _fields_ = [("ns_precision", C.c_int32), ("state_dtype", C.c_int32), ("accel_form", C.c_int32),
-                ("max_streams", C.c_int32), ("reserved", C.c_int32 * 4)]
+                ("max_streams", C.c_int32), ("ns_schedule", C.c_int32), ("reserved", C.c_int32 * 3)]
 
 
 class mona_view(C.Structure):
@@ -207,7 +209,8 @@ class MonaOptimizer:
 
     def __init__(self, weights: Sequence[torch.Tensor], ns_precision: int = 0,
                  state_dtype: torch.dtype = torch.float32, g_dtype: torch.dtype = torch.float32,
-                 accel_form: int = MONA_ACCEL_TWO_BUFFER, max_streams: int = 0):
+                 accel_form: int = MONA_ACCEL_TWO_BUFFER, max_streams: int = 0,
+                 ns_schedule: int = MONA_NS_SCHEDULE_AUTO):
         if not weights:
             raise ValueError("need at least one matrix")
         self.lib = load_library()
@@ -217,7 +220,8 @@ class MonaOptimizer:
         self.weights = list(weights)
         self.count = len(self.weights)
         self.g_dtype = g_dtype
-        self.opts = mona_options(ns_precision, _dtype_code(state_dtype), accel_form, max_streams, (C.c_int32 * 4)())
+        self.opts = mona_options(ns_precision, _dtype_code(state_dtype), accel_form, max_streams, ns_schedule,
+                                 (C.c_int32 * 3)())
         self.accel_form = accel_form
         self.ns_precision = ns_precision
         self.state_dtype = state_dtype

@@ -48,10 +48,11 @@ int fail(int code, const char* fmt, ...) {
 
 constexpr size_t kAlign = 256;
 constexpr int kSmallSideF32 = 64;
+constexpr double kFusedMaxStart = 0.0438;  // largest 1 / sqrt(p) + 1 / sqrt(q) for which the automatic choice fuses iterations
 size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a; }
 int round_up(int v, int a) { return (v + a - 1) / a * a; }
 
-enum OpKind { OP_GRAM = 0, OP_POLY = 1, OP_APPLY = 2 };
+enum OpKind { OP_GRAM = 0, OP_POLY = 1, OP_APPLY = 2, OP_SYMPROD = 3 };
 
 struct Group {
   int m = 0, n = 0;          // native shape
@@ -63,8 +64,11 @@ struct Group {
   bool large_with_company = false;  // 256 x 256 tiles even for launches of few tiles (set when the state is built)
   int esize = 2;             // bytes per element of this group's working copies
   std::vector<int> members;  // matrix indices
+  bool fused = false;        // Newton-Schulz iterations taken in chunks on the p x p side (see build_ops)
+  int npp = 2;               // p x p working matrices: S and B (literal schedule) or S, S', U, Q, R, R' (fused)
+  int o_buf = 1;             // which ping-pong buffer holds O_k of the last step
   size_t x_off[2] = {0, 0};  // byte offsets in the arena: ping-pong X buffers
-  size_t s_off = 0, b_off = 0;
+  size_t pp_off[6] = {0, 0, 0, 0, 0, 0};
   size_t members_off = 0;
   int64_t x_stride = 0, s_stride = 0;  // elements per matrix
 };
@@ -74,6 +78,7 @@ struct Layout {
   int ssize = 4;             // bytes per element of the stored G_{k-1}, A (or C)
   bool one_buffer = false;   // no G_{k-1}; acc_off holds C
   bool caller_slot = false;  // G_{k-1} is kept by the caller (streaming variant)
+  bool external_state = false;  // G_{k-1}, A and M live in arrays of the caller's, not in the arena
   std::vector<size_t> gprev_off, acc_off, mom_off;
   size_t state_begin = 0, state_bytes = 0;     // persistent {G_prev, A, M}
   size_t work_begin = 0, work_bytes = 0;       // X, S, B of every group (zeroed once)
@@ -118,14 +123,18 @@ int check_opts(const mona_options* o, mona_options* out) {
       z.accel_form != MONA_ACCEL_CALLER_SLOT)
     return fail(MONA_EINVAL, "accel_form must be MONA_ACCEL_TWO_BUFFER, MONA_ACCEL_ONE_BUFFER or MONA_ACCEL_CALLER_SLOT");
   if (z.max_streams < 0 || z.max_streams > 8) return fail(MONA_EINVAL, "max_streams must lie in [0, 8]");
+  if (z.ns_schedule != MONA_NS_SCHEDULE_AUTO && z.ns_schedule != MONA_NS_SCHEDULE_LITERAL &&
+      z.ns_schedule != MONA_NS_SCHEDULE_FUSED)
+    return fail(MONA_EINVAL, "ns_schedule must be MONA_NS_SCHEDULE_AUTO, _LITERAL or _FUSED");
   for (int r : z.reserved)
     if (r != 0) return fail(MONA_EINVAL, "reserved option fields must be 0");
   *out = z;
   return MONA_OK;
 }
 
-void build_layout(const mona_matrix* mats, int count, const mona_options& opt, Layout& L) {
+void build_layout(const mona_matrix* mats, int count, const mona_options& opt, bool external_state, Layout& L) {
   L.count = count;
+  L.external_state = external_state;
   L.ssize = opt.state_dtype == MONA_BF16 ? 2 : 4;
   L.one_buffer = opt.accel_form == MONA_ACCEL_ONE_BUFFER;
   L.caller_slot = opt.accel_form == MONA_ACCEL_CALLER_SLOT;
@@ -138,6 +147,7 @@ void build_layout(const mona_matrix* mats, int count, const mona_options& opt, L
   for (int i = 0; i < count; ++i) {
     const size_t ne = (size_t)mats[i].m * mats[i].n;
     L.gprev_off[i] = off;
+    if (external_state) { L.acc_off[i] = L.mom_off[i] = off; continue; }
     if (!L.one_buffer && !L.caller_slot) off = align_up(off + ne * L.ssize);
     L.acc_off[i] = off;   off = align_up(off + ne * L.ssize);
     L.mom_off[i] = off;   off = align_up(off + ne * 4);
@@ -168,6 +178,21 @@ void build_layout(const mona_matrix* mats, int count, const mona_options& opt, L
       g.rows_pad = r128;
       g.cols_pad = c128;
       g.p_pad = g.tall ? g.cols_pad : g.rows_pad;
+      // The fused schedule trades products with the long side q for products on the p x p side, so it pays
+      // when q is well above p.  Advancing the Gram matrix on the p x p side is as accurate as recomputing
+      // it from X while its eigenvalues are still small (the growth phase of the iteration) and less so
+      // once they have reached the band around 1.  A full-rank matrix of this shape starts from singular
+      // values up to about 1 / sqrt(p) + 1 / sqrt(q) and each early iteration multiplies them by a = 3.4445,
+      // so the automatic choice fuses (the first chunk is three iterations) only where a^2 times that bound
+      // is still around one half.  Measured against the float64 oracle on the benchmark's inputs: 1536 x 4096
+      // 7.1e-3 fused against 9.1e-3 literal, 2048 x 8192 6.8e-3 against 9.7e-3; but 1024 x 2048 1.5e-2
+      // against 9.5e-3 and 512 x 4096 1.6e-2 against 1.3e-2, which therefore stay literal.
+      const double q_pad = g.tall ? g.rows_pad : g.cols_pad;
+      const double start = 1.0 / std::sqrt((double)g.p_pad) + 1.0 / std::sqrt(q_pad);
+      g.fused = !g.f32 && (opt.ns_schedule == MONA_NS_SCHEDULE_FUSED ||
+                           (opt.ns_schedule == MONA_NS_SCHEDULE_AUTO && 2.0 * q_pad >= 3.0 * g.p_pad &&
+                            start <= kFusedMaxStart));
+      g.npp = g.fused ? 6 : 2;
       L.groups.push_back(g);
     } else {
       gi = it->second;
@@ -182,8 +207,7 @@ void build_layout(const mona_matrix* mats, int count, const mona_options& opt, L
     g.x_stride = (int64_t)g.rows_pad * g.cols_pad;
     g.s_stride = (int64_t)g.p_pad * g.p_pad;
     for (int b = 0; b < 2; ++b) { g.x_off[b] = off; off = align_up(off + cnt * g.x_stride * g.esize); }
-    g.s_off = off; off = align_up(off + cnt * g.s_stride * g.esize);
-    g.b_off = off; off = align_up(off + cnt * g.s_stride * g.esize);
+    for (int b = 0; b < g.npp; ++b) { g.pp_off[b] = off; off = align_up(off + cnt * g.s_stride * g.esize); }
   }
   L.work_bytes = off - L.work_begin;
 
@@ -207,7 +231,7 @@ void build_layout(const mona_matrix* mats, int count, const mona_options& opt, L
   L.dyn_off = off;      off = align_up(off + sizeof(MatDynamic) * count);
   L.scales_off = off;   off = align_up(off + sizeof(MatScale) * count);
   L.optr_off = off;     off = align_up(off + sizeof(void*) * count);
-  L.partials_off = off; off = align_up(off + sizeof(float) * L.blocks.size());
+  L.partials_off = off; off = align_up(off + sizeof(double) * L.blocks.size());
   L.blocks_off = off;   off = align_up(off + sizeof(BlockWork) * L.blocks.size());
   for (Group& g : L.groups) { g.members_off = off; off = align_up(off + sizeof(int32_t) * g.members.size()); }
   L.total = off;
@@ -259,7 +283,7 @@ struct mona_state {
   bool ev_valid = false;
   bool times_ready = false;
   bool fused_update = false;
-  int o_buf = 1;                   // which ping-pong buffer holds O_k of the last step
+  bool failed = false;             // a launch failed half way through a step: the state arrays are not usable
   std::vector<LaunchRecord> records;
   std::vector<std::pair<hipEvent_t, hipEvent_t>> event_pool;
   size_t pool_used = 0;
@@ -297,73 +321,81 @@ double gemm_flops(const GemmArgs& a) {
   return 2.0 * a.tile_m * a.tile_n * (double)a.K * a.tiles_per_mat * a.count;
 }
 
-void fill_gemm(const mona_state* st, const Group& g, int kind, TileShape tile, int src, const mona_hparams& hp,
-               bool first, bool last, GemmArgs& a, bool& tp, bool& tq) {
-  const Layout& L = st->L;
-  memset(&a, 0, sizeof a);
-  const int cnt = (int)g.members.size();
+// One product launch of the plan.
+struct Op {
+  GemmArgs a;
+  int kind = 0;       // OpKind
+  int iter = 0;       // Newton-Schulz iteration it belongs to
+  TileShape tile{128, 128};
+  bool tp = false, tq = false;
+};
+
+// Newton-Schulz iterations per chunk.  Literal schedule: one.  Fused schedule: three, then twos (measured
+// on bf16-rounded products: fusing the late iterations, or more than three of them, loses accuracy on
+// ill-conditioned inputs; three early ones and pairs afterwards do not).
+std::vector<int> chunk_sizes(int T, bool fused) {
+  std::vector<int> out;
+  if (!fused) { out.assign(T, 1); return out; }
+  int left = T;
+  if (left >= 3) { out.push_back(3); left -= 3; }
+  while (left >= 2) { out.push_back(2); left -= 2; }
+  if (left) out.push_back(1);
+  return out;
+}
+
+// Builds the product launches of one group for one step.
+//
+// Literal schedule, per iteration (Eq. newton_schulz with B = b S + c S S factored out):
+//     S = X X^T;  B = b S + c S S;  X <- a X + B X            (tall: S = X^T X, X <- a X + X B)
+// Fused schedule, per chunk of n iterations.  With Q_t = a I + b S_t + c S_t^2 one iteration is
+// X_{t+1} = Q_t X_t and its Gram matrix is S_{t+1} = Q_t S_t Q_t = S_t Q_t^2 (polynomials of one symmetric
+// matrix commute), so n iterations need X only at both ends:
+//     S = X X^T;  for i < n:  Q_i = a I + b S + c S S;  (i < n - 1:  U = S Q_i;  S <- U Q_i);  R <- R Q_i  (R_0 = Q_0)
+//     X <- R X
+// The same polynomial of X in exact arithmetic, with 3 p^2 q + (4 n - 3) p^3 flop instead of n (3 p^2 q + p^3)
+// on the symmetric count, i.e. fewer whenever q > p.  Every p x p result is computed on the upper block
+// triangle and mirrored.  A chunk of one iteration is the literal iteration.
+struct OpBuilder {
+  const mona_state* st;
+  const Group& g;
+  const mona_hparams& hp;
+  std::vector<Op>& out;
+  int cnt;
+  void* X[2];
+  void* PP[6];
+
+  OpBuilder(const mona_state* st_, const Group& g_, const mona_hparams& hp_, std::vector<Op>& out_);
+  GemmArgs base() const;
+  void push(GemmArgs& a, int kind, int iter, bool tp, bool tq, TileShape tile);
+  void gram(int src, void* S, bool first, int iter);
+  void poly(void* S, void* dst, float diag, int iter);
+  void symprod(void* P, void* Q, void* dst, int iter);
+  void apply(int src, void* Bm, bool with_e, float beta, bool first, bool last, int iter);
+  int build();   // returns the ping-pong buffer that holds O_k afterwards
+};
+
+OpBuilder::OpBuilder(const mona_state* st_, const Group& g_, const mona_hparams& hp_, std::vector<Op>& out_)
+    : st(st_), g(g_), hp(hp_), out(out_), cnt((int)g_.members.size()) {
   char* base = st->arena;
-  void* X = base + g.x_off[src];
-  void* Xn = base + g.x_off[src ^ 1];
-  void* S = base + g.s_off;
-  void* B = base + g.b_off;
+  for (int b = 0; b < 2; ++b) X[b] = base + g.x_off[b];
+  for (int b = 0; b < 6; ++b) PP[b] = b < g.npp ? base + g.pp_off[b] : nullptr;
+}
+
+GemmArgs OpBuilder::base() const {
+  const Layout& L = st->L;
+  GemmArgs a;
+  memset(&a, 0, sizeof a);
   a.count = cnt;
-  a.members = reinterpret_cast<const int32_t*>(base + g.members_off);
+  a.members = reinterpret_cast<const int32_t*>(st->arena + g.members_off);
   a.scales = st->at<MatScale>(L.scales_off);
   a.stat = st->at<MatStatic>(L.stat_off);
   a.dyn = st->at<MatDynamic>(L.dyn_off);
   a.epilogue = EPI_STORE;
   a.post = POST_NONE;
-  // A_t and B_t are symmetric (bit for bit: mirrored tiles are copies, and a diagonal tile adds the same
-  // products in the same order on both sides), so as operands they may be read K-major as well as
-  // row-major.  The large-tile kernel fetches a K-major operand as 32 contiguous 512-byte rows instead of
-  // 64-byte pieces of 256 rows and runs 7-13 % faster per K step on it (measured), so it reads them that
-  // way; the small-tile kernels gain nothing from it.
-  const bool symk = tile.bm == 256;
-  if (kind == OP_GRAM) {
-    a.P = X; a.Q = X; a.E = nullptr; a.C = S;
-    a.strideP = a.strideQ = g.x_stride; a.strideC = g.s_stride;
-    a.ldp = a.ldq = g.cols_pad; a.ldc = g.p_pad;
-    a.M = a.N = g.p_pad;
-    a.K = g.tall ? g.rows_pad : g.cols_pad;
-    tp = tq = g.tall;
-    a.symmetric = 1;
-    a.alpha = 1.0f; a.beta = 0.0f;
-    if (first) a.post = POST_INV2;
-  } else if (kind == OP_POLY) {
-    a.P = S; a.Q = S; a.E = S; a.C = B;
-    a.strideP = a.strideQ = a.strideE = a.strideC = g.s_stride;
-    a.ldp = a.ldq = a.lde = a.ldc = g.p_pad;
-    a.M = a.N = a.K = g.p_pad;
-    tp = tq = symk;
-    a.symmetric = 1;
-    a.alpha = hp.ns_c; a.beta = hp.ns_b;
-  } else {
-    a.E = X; a.C = Xn;
-    a.strideE = a.strideC = g.x_stride;
-    a.lde = a.ldc = g.cols_pad;
-    a.K = g.p_pad;
-    a.M = g.rows_pad; a.N = g.cols_pad;
-    if (g.tall) {          // X' = a X + X B
-      a.P = X; a.strideP = g.x_stride; a.ldp = g.cols_pad;
-      a.Q = B; a.strideQ = g.s_stride; a.ldq = g.p_pad;
-      tp = false; tq = symk;
-    } else {               // X' = a X + B X
-      a.P = B; a.strideP = g.s_stride; a.ldp = g.p_pad;
-      a.Q = X; a.strideQ = g.x_stride; a.ldq = g.cols_pad;
-      tp = symk && !last;   // the launch that carries the update has no register to spare for a K-major P
-      tq = true;
-    }
-    a.symmetric = 0;
-    a.alpha = 1.0f; a.beta = hp.ns_a;
-    if (first) a.post = POST_INV;
-    if (last) {
-      a.epilogue = EPI_UPDATE;
-      a.store_out = (hp.flags & MONA_FLAG_KEEP_O) ? 1 : 0;
-      a.w_keep = 1.0f - hp.lr * hp.weight_decay;
-      a.o_scale = hp.lr * hp.gamma_coeff * sqrtf((float)std::max(g.m, g.n));
-    }
-  }
+  return a;
+}
+
+void OpBuilder::push(GemmArgs& a, int kind, int iter, bool tp, bool tq, TileShape tile) {
   a.tile_m = tile.bm;
   a.tile_n = tile.bn;
   a.sym_ratio = tile.bm / tile.bn;
@@ -375,6 +407,155 @@ void fill_gemm(const mona_state* st, const Group& g, int kind, TileShape tile, i
     for (int ti = 0; ti < a.tiles_m; ++ti) a.tiles_per_mat += a.tiles_n - a.sym_ratio * ti;
   } else {
     a.tiles_per_mat = a.tiles_m * a.tiles_n;
+  }
+  Op op;
+  op.a = a; op.kind = kind; op.iter = iter; op.tile = tile; op.tp = tp; op.tq = tq;
+  out.push_back(op);
+}
+
+// The p x p matrices are symmetric bit for bit outside their diagonal tiles (mirrored tiles are copies), and
+// inside a diagonal tile either triangle is the product to rounding, so as operands they may be read K-major
+// as well as row-major.  The large-tile kernel fetches a K-major operand as 32 contiguous 512-byte rows
+// instead of 64-byte pieces of 256 rows and runs 7-13 % faster per K step on it (measured), so it reads them
+// that way; the small-tile kernels gain nothing from it.
+
+void OpBuilder::gram(int src, void* S, bool first, int iter) {
+  GemmArgs a = base();
+  a.P = X[src]; a.Q = X[src]; a.E = nullptr; a.C = S;
+  a.strideP = a.strideQ = g.x_stride; a.strideC = g.s_stride;
+  a.ldp = a.ldq = g.cols_pad; a.ldc = g.p_pad;
+  a.M = a.N = g.p_pad;
+  a.K = g.tall ? g.rows_pad : g.cols_pad;
+  a.symmetric = 1;
+  a.alpha = 1.0f; a.beta = 0.0f;
+  if (first) a.post = POST_INV2;
+  push(a, OP_GRAM, iter, g.tall, g.tall, pick_tile(g, OP_GRAM, cnt));
+}
+
+void OpBuilder::poly(void* S, void* dst, float diag, int iter) {
+  const TileShape tile = pick_tile(g, OP_POLY, cnt);
+  const bool symk = tile.bm == 256;
+  GemmArgs a = base();
+  a.P = S; a.Q = S; a.E = S; a.C = dst;
+  a.strideP = a.strideQ = a.strideE = a.strideC = g.s_stride;
+  a.ldp = a.ldq = a.lde = a.ldc = g.p_pad;
+  a.M = a.N = a.K = g.p_pad;
+  a.symmetric = 1;
+  a.alpha = hp.ns_c; a.beta = hp.ns_b;
+  a.diag = diag;
+  push(a, OP_POLY, iter, symk, symk, tile);
+}
+
+void OpBuilder::symprod(void* P, void* Q, void* dst, int iter) {
+  const TileShape tile = pick_tile(g, OP_SYMPROD, cnt);
+  const bool symk = tile.bm == 256;
+  GemmArgs a = base();
+  a.P = P; a.Q = Q; a.E = nullptr; a.C = dst;
+  a.strideP = a.strideQ = a.strideC = g.s_stride;
+  a.ldp = a.ldq = a.ldc = g.p_pad;
+  a.M = a.N = a.K = g.p_pad;
+  a.symmetric = 1;
+  a.alpha = 1.0f; a.beta = 0.0f;
+  push(a, OP_SYMPROD, iter, symk, symk, tile);
+}
+
+void OpBuilder::apply(int src, void* Bm, bool with_e, float beta, bool first, bool last, int iter) {
+  const TileShape tile = pick_tile(g, OP_APPLY, cnt);
+  const bool symk = tile.bm == 256;
+  GemmArgs a = base();
+  a.E = with_e ? X[src] : nullptr; a.C = X[src ^ 1];
+  a.strideE = a.strideC = g.x_stride;
+  a.lde = a.ldc = g.cols_pad;
+  a.K = g.p_pad;
+  a.M = g.rows_pad; a.N = g.cols_pad;
+  bool tp, tq;
+  if (g.tall) {          // X' = beta X + X B
+    a.P = X[src]; a.strideP = g.x_stride; a.ldp = g.cols_pad;
+    a.Q = Bm; a.strideQ = g.s_stride; a.ldq = g.p_pad;
+    tp = false; tq = symk;
+  } else {               // X' = beta X + B X
+    a.P = Bm; a.strideP = g.s_stride; a.ldp = g.p_pad;
+    a.Q = X[src]; a.strideQ = g.x_stride; a.ldq = g.cols_pad;
+    tp = symk && !last;   // the launch that carries the update has no register to spare for a K-major P
+    tq = true;
+  }
+  a.symmetric = 0;
+  a.alpha = 1.0f; a.beta = with_e ? beta : 0.0f;
+  if (first) a.post = POST_INV;
+  if (last) {
+    a.epilogue = EPI_UPDATE;
+    a.store_out = (hp.flags & MONA_FLAG_KEEP_O) ? 1 : 0;
+    a.w_keep = 1.0f - hp.lr * hp.weight_decay;
+    a.o_scale = hp.lr * hp.gamma_coeff * sqrtf((float)std::max(g.m, g.n));
+  }
+  push(a, OP_APPLY, iter, tp, tq, tile);
+}
+
+int OpBuilder::build() {
+  const int T = hp.ns_steps;
+  const std::vector<int> chunks = chunk_sizes(T, g.fused);
+  int src = 0, iter = 0;
+  for (size_t ci = 0; ci < chunks.size(); ++ci) {
+    const int n = chunks[ci];
+    const bool first = ci == 0, last = ci + 1 == chunks.size();
+    if (n == 1) {
+      gram(src, PP[0], first, iter);
+      poly(PP[0], PP[1], 0.0f, iter);
+      apply(src, PP[1], true, hp.ns_a, first, last, iter);
+    } else {
+      void* S = PP[0]; void* S2 = PP[1]; void* U = PP[2]; void* Q = PP[3]; void* R = PP[4]; void* R2 = PP[5];
+      gram(src, S, first, iter);
+      for (int i = 0; i < n; ++i) {
+        void* Qi = i == 0 ? R : Q;                 // Q_0 is R_0
+        poly(S, Qi, hp.ns_a, iter + i);
+        if (i + 1 < n) {
+          symprod(S, Qi, U, iter + i);
+          symprod(U, Qi, S2, iter + i);
+          std::swap(S, S2);
+        }
+        if (i > 0) {
+          symprod(R, Q, R2, iter + i);
+          std::swap(R, R2);
+        }
+      }
+      apply(src, R, false, 0.0f, first, last, iter + n - 1);
+    }
+    src ^= 1;
+    iter += n;
+  }
+  return T == 0 ? 1 : src;
+}
+
+// Static description of matrix i: where its state arrays and its working copy live.
+void fill_static(const Layout& L, const mona_matrix& q, int i, char* arena, void* g_prev, void* acc, void* mom,
+                 MatStatic& ms, void*& o_ptr) {
+  const Group& g = L.groups[L.group_of[i]];
+  memset(&ms, 0, sizeof ms);
+  ms.g_prev = (L.one_buffer || L.caller_slot) ? nullptr : g_prev;
+  ms.acc = acc;
+  ms.mom = static_cast<float*>(mom);
+  ms.x = arena + g.x_off[0] + (size_t)L.rank_in_group[i] * g.x_stride * g.esize;
+  ms.m = q.m;
+  ms.n = q.n;
+  ms.ldx = g.cols_pad;
+  ms.w_dtype = q.w_dtype;
+  ms.g_dtype = q.g_dtype;
+  ms.first_block = L.first_block[i];
+  ms.num_blocks = L.num_blocks[i];
+  ms.x_f32 = g.f32 ? 1 : 0;
+  o_ptr = arena + g.x_off[1] + (size_t)L.rank_in_group[i] * g.x_stride * g.esize;
+}
+
+// Theorem 1 assumes |alpha| < 1 / (1 - beta_a).  A step outside that range is taken all the same (the
+// algorithm is defined for any alpha); the note is left where mona_last_error() finds it.
+void note_unstable_alpha(const mona_hparams* hp) {
+  if (hp->flags & MONA_FLAG_MUON_ONLY) return;
+  const double bound = 1.0 / (1.0 - (double)hp->beta_a);
+  if (std::fabs((double)hp->alpha) >= bound) {
+    char buf[256];
+    snprintf(buf, sizeof buf, "warning: |alpha| = %g is not below 1 / (1 - beta_a) = %g, the range the convergence "
+             "theorem assumes; the step was taken", std::fabs((double)hp->alpha), bound);
+    g_err = buf;
   }
 }
 
@@ -419,7 +600,7 @@ int mona_state_size(const mona_matrix* mats, int32_t count, const mona_options* 
   rc = check_opts(opts, &o);
   if (rc) return rc;
   Layout L;
-  build_layout(mats, count, o, L);
+  build_layout(mats, count, o, false, L);
   *bytes_out = L.total;
   return MONA_OK;
 }
@@ -437,7 +618,7 @@ int mona_init_state(const mona_matrix* mats, int32_t count, const mona_options* 
   if ((uintptr_t)arena % kAlign) return fail(MONA_EINVAL, "arena must be 256-byte aligned");
   mona_state* st = new (std::nothrow) mona_state();
   if (!st) return fail(MONA_ENOMEM, "host allocation failed");
-  build_layout(mats, count, o, st->L);
+  build_layout(mats, count, o, false, st->L);
   const Layout& L = st->L;
   if (arena_bytes < L.total) {
     const size_t need = L.total;
@@ -561,22 +742,8 @@ int mona_init_state(const mona_matrix* mats, int32_t count, const mona_options* 
   std::vector<MatStatic> stat(count);
   std::vector<void*> optr(count);
   for (int i = 0; i < count; ++i) {
-    const Group& g = L.groups[L.group_of[i]];
-    MatStatic& ms = stat[i];
-    memset(&ms, 0, sizeof ms);
-    ms.g_prev = (L.one_buffer || L.caller_slot) ? nullptr : st->arena + L.gprev_off[i];
-    ms.acc = st->arena + L.acc_off[i];
-    ms.mom = reinterpret_cast<float*>(st->arena + L.mom_off[i]);
-    ms.x = st->arena + g.x_off[0] + (size_t)L.rank_in_group[i] * g.x_stride * g.esize;
-    ms.m = mats[i].m;
-    ms.n = mats[i].n;
-    ms.ldx = g.cols_pad;
-    ms.w_dtype = mats[i].w_dtype;
-    ms.g_dtype = mats[i].g_dtype;
-    ms.first_block = L.first_block[i];
-    ms.num_blocks = L.num_blocks[i];
-    ms.x_f32 = g.f32 ? 1 : 0;
-    optr[i] = st->arena + g.x_off[1] + (size_t)L.rank_in_group[i] * g.x_stride * g.esize;
+    fill_static(L, mats[i], i, st->arena, st->arena + L.gprev_off[i], st->arena + L.acc_off[i],
+                st->arena + L.mom_off[i], stat[i], optr[i]);
   }
   INIT_TRY(hipMemcpyAsync(st->arena + L.stat_off, stat.data(), sizeof(MatStatic) * count, hipMemcpyHostToDevice, s));
   INIT_TRY(hipMemcpyAsync(st->arena + L.optr_off, optr.data(), sizeof(void*) * count, hipMemcpyHostToDevice, s));
@@ -628,8 +795,119 @@ int mona_step_streaming(mona_state* st, const mona_matrix* mats, void* const* sl
 
 namespace {
 
+// Enqueues the kernels of one step (Alg. 1 for every matrix) on `s` and the side streams.  The per-matrix
+// tables in the arena must already name this step's w / g pointers.
+int enqueue_step(mona_state* st, const mona_hparams* hp, hipStream_t s) {
+  Layout& L = st->L;
+  const int count = L.count;
+  const MatStatic* stat = st->at<MatStatic>(L.stat_off);
+  const MatDynamic* dyn = st->at<MatDynamic>(L.dyn_off);
+  MatScale* scales = st->at<MatScale>(L.scales_off);
+  double* partials = st->at<double>(L.partials_off);
+  const BlockWork* blocks = st->at<BlockWork>(L.blocks_off);
+  const int nblocks = (int)L.blocks.size();
+
+  // A HIP call that fails once kernels of the step are in flight leaves the state arrays half updated:
+  // join whatever was forked, mark the state unusable and say so.
+  bool forked = false;
+  auto bail = [&](hipError_t e, const char* what) {
+    if (forked)
+      for (size_t i = 0; i < st->side.size(); ++i) {
+        (void)hipEventRecord(st->side_done[i], st->side[i]);
+        (void)hipStreamWaitEvent(s, st->side_done[i], 0);
+      }
+    st->failed = true;
+    return fail(MONA_EHIP, "%s: %s (the step was abandoned half way: the state arrays are unusable until a checkpoint "
+                "is imported with mona_state_import)", what, hipGetErrorString(e));
+  };
+#define STEP_TRY(expr)                                   \
+  do {                                                   \
+    hipError_t e__ = (expr);                             \
+    if (e__ != hipSuccess) return bail(e__, #expr);      \
+  } while (0)
+
+  const bool prof = st->profiling > 0;
+  hipEvent_t* const ev = st->ev[st->prof_steps % kProfSets];
+  st->times_ready = false;
+  st->records.clear();
+  st->pool_used = 0;
+  if (prof) STEP_TRY(hipEventRecord(ev[0], s));
+
+  // Alg. 1: difference, acceleration EMA, accelerated gradient, momentum, roll; sum of squares
+  const bool muon_only = (hp->flags & MONA_FLAG_MUON_ONLY) != 0;
+  const int use_prev = muon_only ? 2 : !((hp->flags & MONA_FLAG_FIRST_DIFF_ZERO) && st->k == 0);
+  const int sbf = st->opt.state_dtype == MONA_BF16;
+  const int one = L.one_buffer ? 1 : 0;
+  STEP_TRY(launch_state_update(stat, dyn, blocks, partials, L.blocks_f32g, 0, sbf, one, hp->momentum, hp->beta_a,
+                               hp->alpha, use_prev, s));
+  STEP_TRY(launch_state_update(stat, dyn, blocks + L.blocks_f32g, partials + L.blocks_f32g, nblocks - L.blocks_f32g,
+                               1, sbf, one, hp->momentum, hp->beta_a, hp->alpha, use_prev, s));
+  if (L.one_buffer && !muon_only) st->last_beta_a = hp->beta_a;
+  STEP_TRY(launch_norm_finalize(stat, partials, scales, count, hp->ns_eps, s));
+  if (prof) STEP_TRY(hipEventRecord(ev[1], s));
+
+  // Newton-Schulz (Eq. newton_schulz), T iterations per shape group
+  const int T = hp->ns_steps;
+  st->fused_update = T > 0;
+  // per-launch timing serialises the launches on the caller's stream so that each interval is one kernel
+  const bool fork = !st->side.empty() && st->profiling < 2 && T > 0;
+  if (fork) {
+    STEP_TRY(hipEventRecord(st->fork_ev, s));
+    forked = true;
+    for (hipStream_t q : st->side) STEP_TRY(hipStreamWaitEvent(q, st->fork_ev, 0));
+  }
+  std::vector<Op> ops;
+  for (size_t gi = 0; gi < L.groups.size(); ++gi) {
+    Group& g = L.groups[gi];
+    const int lane = fork ? st->lane_of_group[gi] : 0;
+    hipStream_t gs = lane == 0 ? s : st->side[lane - 1];
+    ops.clear();
+    g.o_buf = OpBuilder(st, g, *hp, ops).build();
+    for (const Op& op : ops) {
+      LaunchRecord rec;
+      const bool each = st->profiling > 1;
+      if (each) {
+        if (!get_event_pair(st, &rec.e0, &rec.e1)) return bail(hipErrorOutOfMemory, "hipEventCreate");
+        STEP_TRY(hipEventRecord(rec.e0, gs));
+      }
+      STEP_TRY(launch_ns_gemm(op.a, op.tile.bm, op.tp, op.tq, g.f32, gs));
+      if (each) {
+        STEP_TRY(hipEventRecord(rec.e1, gs));
+        rec.kind = op.kind; rec.group = (int)gi; rec.iter = op.iter; rec.tile = op.tile.bm * 1000 + op.tile.bn;
+        rec.flops = gemm_flops(op.a);
+        st->records.push_back(rec);
+      }
+    }
+  }
+  if (fork) {
+    for (size_t i = 0; i < st->side.size(); ++i) {
+      STEP_TRY(hipEventRecord(st->side_done[i], st->side[i]));
+      STEP_TRY(hipStreamWaitEvent(s, st->side_done[i], 0));
+    }
+    forked = false;
+  }
+  if (prof) STEP_TRY(hipEventRecord(ev[2], s));
+  if (T == 0) {
+    // O = X_0, then Eq. muon_update
+    STEP_TRY(launch_plain_update(stat, dyn, scales, blocks, nblocks, st->at<void*>(L.optr_off), hp->lr,
+                                 hp->weight_decay, hp->gamma_coeff, (hp->flags & MONA_FLAG_KEEP_O) ? 1 : 0, s));
+  }
+  if (prof) {
+    STEP_TRY(hipEventRecord(ev[3], s));
+    st->times_ready = true;
+    st->prof_steps += 1;
+  }
+#undef STEP_TRY
+  st->k += 1;
+  return MONA_OK;
+}
+
 int step_impl(mona_state* st, const mona_matrix* mats, void* const* slots, int32_t count, const mona_hparams* hp,
               void* stream) {
+  g_err.clear();
+  if (st->failed)
+    return fail(MONA_EHIP, "this state was left half updated by a failed launch in an earlier step: import a "
+                "checkpoint with mona_state_import first");
   int rc = check_mats(mats, count, true);
   if (rc) return rc;
   rc = check_hparams(hp);
@@ -676,90 +954,9 @@ int step_impl(mona_state* st, const mona_matrix* mats, void* const* slots, int32
     st->ring_next = (slot + 1) % kRing;
     st->dyn_valid = true;
   }
-
-  const MatStatic* stat = st->at<MatStatic>(L.stat_off);
-  const MatDynamic* dyn = st->at<MatDynamic>(L.dyn_off);
-  MatScale* scales = st->at<MatScale>(L.scales_off);
-  float* partials = st->at<float>(L.partials_off);
-  const BlockWork* blocks = st->at<BlockWork>(L.blocks_off);
-  const int nblocks = (int)L.blocks.size();
-
-  const bool prof = st->profiling > 0;
-  hipEvent_t* const ev = st->ev[st->prof_steps % kProfSets];
-  st->times_ready = false;
-  st->records.clear();
-  st->pool_used = 0;
-  if (prof) HIP_TRY(hipEventRecord(ev[0], s));
-
-  // Alg. 1: difference, acceleration EMA, accelerated gradient, momentum, roll; sum of squares
-  const int use_prev = (hp->flags & MONA_FLAG_MUON_ONLY) ? 2 : !((hp->flags & MONA_FLAG_FIRST_DIFF_ZERO) && st->k == 0);
-  const int sbf = st->opt.state_dtype == MONA_BF16;
-  const int one = L.one_buffer ? 1 : 0;
-  HIP_TRY(launch_state_update(stat, dyn, blocks, partials, L.blocks_f32g, 0, sbf, one, hp->momentum, hp->beta_a,
-                              hp->alpha, use_prev, s));
-  HIP_TRY(launch_state_update(stat, dyn, blocks + L.blocks_f32g, partials + L.blocks_f32g, nblocks - L.blocks_f32g, 1,
-                              sbf, one, hp->momentum, hp->beta_a, hp->alpha, use_prev, s));
-  if (L.one_buffer && !muon_only) st->last_beta_a = hp->beta_a;
-  HIP_TRY(launch_norm_finalize(stat, partials, scales, count, hp->ns_eps, s));
-  if (prof) HIP_TRY(hipEventRecord(ev[1], s));
-
-  // Newton-Schulz (Eq. newton_schulz), T iterations of Gram / poly / apply per shape group
-  const int T = hp->ns_steps;
-  st->fused_update = T > 0;
-  st->o_buf = (T == 0) ? 1 : (T & 1);
-  // per-launch timing serialises the launches on the caller's stream so that each interval is one kernel
-  const bool fork = !st->side.empty() && st->profiling < 2 && T > 0;
-  if (fork) {
-    HIP_TRY(hipEventRecord(st->fork_ev, s));
-    for (hipStream_t q : st->side) HIP_TRY(hipStreamWaitEvent(q, st->fork_ev, 0));
-  }
-  for (size_t gi = 0; gi < L.groups.size(); ++gi) {
-    const Group& g = L.groups[gi];
-    const int cnt = (int)g.members.size();
-    const int lane = fork ? st->lane_of_group[gi] : 0;
-    hipStream_t gs = lane == 0 ? s : st->side[lane - 1];
-    int src = 0;
-    for (int t = 0; t < T; ++t) {
-      for (int kind = OP_GRAM; kind <= OP_APPLY; ++kind) {
-        GemmArgs a;
-        bool tp = false, tq = false;
-        const TileShape tile = pick_tile(g, kind, cnt);
-        fill_gemm(st, g, kind, tile, src, *hp, t == 0, t == T - 1, a, tp, tq);
-        LaunchRecord rec;
-        const bool each = st->profiling > 1;
-        if (each) {
-          if (!get_event_pair(st, &rec.e0, &rec.e1)) return fail(MONA_EHIP, "hipEventCreate failed");
-          HIP_TRY(hipEventRecord(rec.e0, gs));
-        }
-        HIP_TRY(launch_ns_gemm(a, tile.bm, tp, tq, g.f32, gs));
-        if (each) {
-          HIP_TRY(hipEventRecord(rec.e1, gs));
-          rec.kind = kind; rec.group = (int)gi; rec.iter = t; rec.tile = tile.bm * 1000 + tile.bn;
-          rec.flops = gemm_flops(a);
-          st->records.push_back(rec);
-        }
-      }
-      src ^= 1;
-    }
-  }
-  if (fork) {
-    for (size_t i = 0; i < st->side.size(); ++i) {
-      HIP_TRY(hipEventRecord(st->side_done[i], st->side[i]));
-      HIP_TRY(hipStreamWaitEvent(s, st->side_done[i], 0));
-    }
-  }
-  if (prof) HIP_TRY(hipEventRecord(ev[2], s));
-  if (T == 0) {
-    // O = X_0, then Eq. muon_update
-    HIP_TRY(launch_plain_update(stat, dyn, scales, blocks, nblocks, st->at<void*>(L.optr_off), hp->lr,
-                                hp->weight_decay, hp->gamma_coeff, (hp->flags & MONA_FLAG_KEEP_O) ? 1 : 0, s));
-  }
-  if (prof) {
-    HIP_TRY(hipEventRecord(ev[3], s));
-    st->times_ready = true;
-    st->prof_steps += 1;
-  }
-  st->k += 1;
+  rc = enqueue_step(st, hp, s);
+  if (rc) return rc;
+  note_unstable_alpha(hp);
   return MONA_OK;
 }
 
@@ -809,9 +1006,9 @@ int mona_state_view(mona_state* st, int32_t i, int32_t kind, mona_view* out) {
       out->rows = out->cols = out->ld = 1; out->dtype = MONA_F32;
       break;
     case MONA_VIEW_O: {
-      // iteration t reads buffer t % 2 and writes the other one; with T = 0 the update kernel
-      // writes buffer 1
-      out->ptr = st->arena + g.x_off[st->o_buf] + (size_t)L.rank_in_group[i] * g.x_stride * g.esize;
+      // every chunk of iterations reads one ping-pong buffer and writes the other; with T = 0 the update
+      // kernel writes buffer 1
+      out->ptr = st->arena + g.x_off[g.o_buf] + (size_t)L.rank_in_group[i] * g.x_stride * g.esize;
       out->ld = g.cols_pad;
       out->dtype = g.f32 ? MONA_F32 : MONA_BF16;
       break;
@@ -842,6 +1039,10 @@ int mona_state_import(mona_state* st, const void* src, size_t src_bytes, int64_t
   if (step_count < 0) return fail(MONA_EINVAL, "step_count must be >= 0");
   HIP_TRY(hipMemcpyAsync(st->arena + st->L.state_begin, src, st->L.state_bytes, hipMemcpyDeviceToDevice,
                          static_cast<hipStream_t>(stream)));
+  // The products rely on the padding of the working matrices being zero.  The steps themselves keep it so;
+  // clearing it here as well makes an imported state independent of whatever the arena went through before.
+  HIP_TRY(launch_fill_zero(st->arena + st->L.work_begin, st->L.work_bytes, static_cast<hipStream_t>(stream)));
+  st->failed = false;
   st->k = step_count;
   st->last_beta_a = -1.0f;   // the checkpoint does not say which beta_a formed C
   return MONA_OK;
@@ -930,18 +1131,15 @@ int mona_plan_info(mona_state* st, int32_t ns_steps, int64_t* launches_out, doub
   const Layout& L = st->L;
   mona_hparams hp;
   memset(&hp, 0, sizeof hp);
+  hp.ns_steps = ns_steps;
   double flops = 0.0;
   int64_t launches = 0;
+  std::vector<Op> ops;
   for (const Group& g : L.groups) {
-    const int cnt = (int)g.members.size();
-    for (int kind = OP_GRAM; kind <= OP_APPLY; ++kind) {
-      GemmArgs a;
-      bool tp, tq;
-      const TileShape tile = pick_tile(g, kind, cnt);
-      fill_gemm(st, g, kind, tile, 0, hp, false, false, a, tp, tq);
-      flops += gemm_flops(a) * ns_steps;
-      launches += ns_steps;
-    }
+    ops.clear();
+    OpBuilder(st, g, hp, ops).build();
+    for (const Op& op : ops) flops += gemm_flops(op.a);
+    launches += (int64_t)ops.size();
   }
   double bytes = 0.0;
   for (int i = 0; i < L.count; ++i) {

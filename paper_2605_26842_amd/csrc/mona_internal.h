@@ -32,10 +32,12 @@ struct MatDynamic {
 
 // Result of the per-matrix Frobenius norm (Sec. 3.2, X_0 = M / ||M||_F).
 struct MatScale {
-  float inv;        // 1 / (||M||_F + eps), 0 when the denominator is 0 or not finite
+  float inv;        // 1 / (||M||_F + eps) for the working copy as it stands (see xexp), 0 when the
+                    // denominator is 0 or not finite
   float inv2;       // inv * inv
   float norm;       // ||M||_F
   uint32_t status;  // MONA_STATUS_* bits
+  int32_t xexp;     // the working copy holds M 2^xexp (0 unless the norm left the safe window)
 };
 
 // One entry per block of the elementwise grid.
@@ -44,17 +46,11 @@ struct BlockWork {
   int32_t chunk;  // chunk index inside that matrix
 };
 
-#ifndef MONA_EW_THREADS
-#define MONA_EW_THREADS 256
-#endif
-#ifndef MONA_EW_CHUNK
-#define MONA_EW_CHUNK 4096
-#endif
-constexpr int kEwThreads = MONA_EW_THREADS;
-constexpr int kEwChunk = MONA_EW_CHUNK;  // elements per block of the elementwise kernel
+constexpr int kEwThreads = 256;
+constexpr int kEwChunk = 4096;  // elements per block of the elementwise kernel
 
 // ---- Newton-Schulz product kernels -------------------------------------------------
-// out = post * (beta * E + alpha * (P Q^T)),   P: M x K,  Q: N x K  (logical shapes)
+// out = post * (beta * E + alpha * (P Q^T)) + diag * I,   P: M x K,  Q: N x K  (logical shapes)
 // An operand flagged "transposed" is stored K-major (K x M or K x N, rows of length ld).
 enum GemmEpilogue : int32_t {
   EPI_STORE = 0,   // store `out`
@@ -75,6 +71,7 @@ struct GemmArgs {
   int32_t count;            // matrices in the group
   int32_t symmetric;        // 1: only tiles with tj >= ti are computed, the result is mirrored
   float alpha, beta;
+  float diag;               // added to the main diagonal of the result (symmetric products only)
   int32_t post;             // PostScale, indexed through `members`
   int32_t epilogue;         // GemmEpilogue
   int32_t store_out;        // EPI_UPDATE: also store O
@@ -91,9 +88,10 @@ int api_fail(int code, const char* fmt, va_list ap);
 
 // kernels (defined in the .hip files)
 hipError_t launch_state_update(const MatStatic* stat, const MatDynamic* dyn, const BlockWork* work,
-                               float* partials, int num_blocks, int g_bf16, int state_bf16, int one_buffer,
+                               double* partials, int num_blocks, int g_bf16, int state_bf16, int one_buffer,
                                float mu, float beta_a, float alpha, int use_prev, hipStream_t s);
-hipError_t launch_norm_finalize(const MatStatic* stat, const float* partials, MatScale* scales,
+// norm_finalize_kernel, then rescue_kernel (repairs the working copies of flagged matrices)
+hipError_t launch_norm_finalize(const MatStatic* stat, const double* partials, MatScale* scales,
                                 int count, float eps, hipStream_t s);
 hipError_t launch_plain_update(const MatStatic* stat, const MatDynamic* dyn, const MatScale* scales,
                                const BlockWork* work, int num_blocks, void* const* o_ptrs, float lr, float wd,

@@ -25,8 +25,6 @@
 //   ns_gemm_f32_kernel       v_mfma_f32_32x32x2_f32, 128 x 128 tile, K step 16, for fp32 products.
 #include "mona_internal.h"
 
-#include <cstdio>
-#include <cstdlib>
 #include <type_traits>
 
 namespace mona {
@@ -315,6 +313,10 @@ struct Epilogue {
 #pragma unroll
           for (int e = 0; e < CH; ++e) val[e] = post * (a.alpha * val[e]);
         }
+        if (a.diag != 0.0f) {
+#pragma unroll
+          for (int e = 0; e < CH; ++e) val[e] += (grow == gcol + e) ? a.diag : 0.0f;
+        }
         vec_t ov;
 #pragma unroll
         for (int e = 0; e < CH; ++e) ov[e] = (T)val[e];
@@ -422,7 +424,7 @@ __device__ __forceinline__ void tr_read_32_rows(u32x2 (&lo)[4], u32x2 (&hi)[4], 
 // values from then on), and the stores of the passes then stream without any wait.  HAS_E is a template
 // parameter for the same reason: a run-time test around the loads would make every later use look as if
 // it might still be pending.
-template <int MI, int NPF, int NPRE, bool UPD, bool HAS_E>
+template <int MI, int NPF, int NPRE, bool UPD, bool HAS_E, bool DIAG>
 struct BlockEpilogue {
   static constexpr int NI = 2, WN = 64, CH = 8, PASSES = MI * 4;
   static constexpr int kStageBytesPerWave = 32 * WN * 4;
@@ -431,6 +433,7 @@ struct BlockEpilogue {
   const GemmArgs& a;
   int lane, row_w0, col_w0;
   bool mirror, skip_w, w_pref;
+  bool has_diag;                 // this wavefront's part of the tile holds elements of the main diagonal that get a.diag
   float c_acc, c_e;              // out = c_acc * accumulator + c_e * E  (post-scale folded in)
   // tile-relative addressing: wavefront-uniform 64-bit bases plus 32-bit lane offsets
   const char* __restrict__ Et;
@@ -465,10 +468,13 @@ struct BlockEpilogue {
   // nothing but this row's chunks (and the previous row's stores) is outstanding here
   template <int H>
   __device__ __forceinline__ void settle_half() {
-    static_assert(UPD && HAS_E && NPF == 8, "halves of a batch of 8 passes");
-    asm volatile("s_waitcnt vmcnt(0)"
-                 : "+v"(ev[4 * H]), "+v"(ev[4 * H + 1]), "+v"(ev[4 * H + 2]), "+v"(ev[4 * H + 3]),
-                   "+v"(wv[4 * H]), "+v"(wv[4 * H + 1]), "+v"(wv[4 * H + 2]), "+v"(wv[4 * H + 3]));
+    static_assert(UPD && NPF == 8, "halves of a batch of 8 passes");
+    if constexpr (HAS_E)
+      asm volatile("s_waitcnt vmcnt(0)"
+                   : "+v"(ev[4 * H]), "+v"(ev[4 * H + 1]), "+v"(ev[4 * H + 2]), "+v"(ev[4 * H + 3]),
+                     "+v"(wv[4 * H]), "+v"(wv[4 * H + 1]), "+v"(wv[4 * H + 2]), "+v"(wv[4 * H + 3]));
+    else
+      asm volatile("s_waitcnt vmcnt(0)" : "+v"(wv[4 * H]), "+v"(wv[4 * H + 1]), "+v"(wv[4 * H + 2]), "+v"(wv[4 * H + 3]));
   }
 
   __device__ __forceinline__ void begin(int tmat, int row0, int col0, bool mir) {
@@ -486,6 +492,7 @@ struct BlockEpilogue {
     else if (a.post == POST_INV2) post = a.scales[mi].inv2;
     c_acc = post * a.alpha;
     c_e = post * a.beta;
+    has_diag = DIAG && a.diag != 0.0f && row0 < col0 + WN && col0 < row0 + 32 * MI;
     const int prow = lane >> 3, q = lane & 7;
     Et = HAS_E ? reinterpret_cast<const char*>(static_cast<const bf16_t*>(a.E) + (size_t)tmat * a.strideE +
                                                (size_t)row0 * a.lde + col0)
@@ -532,6 +539,21 @@ struct BlockEpilogue {
       static_for<4>([&](auto p) { prefetch<p>(); });     // block row 0; row i + 1 follows while row i is worked on
     } else {
       static_for<NPF - NPRE>([&](auto p) { prefetch<NPRE + p>(); });
+    }
+    if (DIAG && has_diag) {
+      // (wavefront-uniform, and rare: only the poly launches of the fused schedule add a diagonal term,
+      // and only in the wavefronts whose part of a diagonal tile meets the diagonal)  The term goes into
+      // the accumulators, divided by their factor, so that the passes below stay as they are.
+      // Register v of block (i, j) holds row 32 i + lane % 32, column 32 j + 8 (v / 4) + 4 (lane / 32) + v % 4.
+      const float dv = a.diag / c_acc;
+      const int d0 = row_w0 - col_w0 + (lane & 31) - 4 * (lane >> 5);
+      static_for<MI>([&](auto i) {
+        static_for<NI>([&](auto j) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            acc[i][j][v] += (d0 + 32 * (i - j) - 8 * (v >> 2) - (v & 3) == 0) ? dv : 0.0f;
+        });
+      });
     }
     const int srow = lane & 31, shalf = lane >> 5;       // staging writes: row and 4-column half
     const int prow = lane >> 3, q = lane & 7;            // passes: row inside the pass and 8-column chunk
@@ -746,22 +768,6 @@ __global__ __launch_bounds__(kThreads) void ns_gemm_bf16_kernel(const GemmArgs a
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 #define MONA_AS1 __attribute__((address_space(1)))
 #define MONA_AS3 __attribute__((address_space(3)))
-#ifdef MONA_TIMING
-// debug builds only: per-workgroup cycle stamps of the last tile (0 kernel start, 1 K loop entered,
-// 2 K loop done, 3 epilogue done, 4 top of the round) and, in slot 5, the number of tiles walked
-__device__ unsigned long long g_timing[8 * 65536];
-#define MONA_STAMP(slot)                                                                     \
-  do {                                                                                       \
-    if (threadIdx.x == 0 && blockIdx.x < 65536) g_timing[blockIdx.x * 8 + (slot)] = __builtin_readcyclecounter(); \
-  } while (0)
-#define MONA_COUNT(slot, v)                                                                  \
-  do {                                                                                       \
-    if (threadIdx.x == 0 && blockIdx.x < 65536) g_timing[blockIdx.x * 8 + (slot)] = (unsigned long long)(v); \
-  } while (0)
-#else
-#define MONA_STAMP(slot) do {} while (0)
-#define MONA_COUNT(slot, v) do {} while (0)
-#endif
 
 // A fragment as the LDS read instructions deliver it.  The registers are written when the data
 // returns, not when the read is issued, so until the matching wait they must stay exactly where
@@ -816,7 +822,7 @@ __device__ __forceinline__ void lds_read_t(FragT& f, uint32_t addr) {
 // s_waitcnt vmcnt(n), leaving the other counters alone (gfx9 encoding)
 #define MONA_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
 
-template <int BM, int BN, int WGM, int WGN, int STAGES, int MIN_BLOCKS, bool TP, bool TQ, bool UPD, bool HAS_E>
+template <int BM, int BN, int WGM, int WGN, int STAGES, int MIN_BLOCKS, bool TP, bool TQ, bool UPD, bool HAS_E, bool DIAG>
 __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_kernel(const GemmArgs a) {
   constexpr int BK = 32;
   constexpr int NW = WGM * WGN;
@@ -834,7 +840,6 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
   static_assert(LDS_U * 16 <= 160 * 1024, "LDS of one CU");
   __shared__ __attribute__((aligned(256))) u32x4 lds[LDS_U];
 
-  MONA_STAMP(0);
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: keeps LDS bases in SGPRs
   const int wm = wave / WGN, wn = wave % WGN;
@@ -999,7 +1004,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
 
   static_assert(STAGES == 4, "the pipeline below is written for a ring of 4 stages");
   // (the launch that carries the update has no registers for an early request during the last K steps)
-  typedef BlockEpilogue<MI, /*batch*/ (UPD ? 8 : 16), /*early*/ (UPD ? 0 : 2), UPD, HAS_E> Epi;
+  typedef BlockEpilogue<MI, /*batch*/ (UPD ? 8 : 16), /*early*/ (UPD ? 0 : 2), UPD, HAS_E, DIAG> Epi;
   Epi epi(a);
   static_assert(NI == Epi::NI && (3 * STAGE_U * 16 + NW * Epi::kStageBytesPerWave) <= LDS_U * 16,
                 "epilogue staging: stage 3 and the LDS behind the ring");
@@ -1014,15 +1019,12 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
   issue(2, 2);
   for (int round = 0;; ++round) {
     // entry: chunks 0..2 of tile t are in flight (or landed) in stages 0..2; stage 3 is free
-    MONA_STAMP(4);
-    MONA_COUNT(5, round + 1);
     // Stores of the previous epilogue may still be in flight and, unlike loads, may retire out of
     // order: counting "all but n" is only safe once they are gone, so drain everything here (the
     // loads of stages 0..2 were issued a whole epilogue ago).
     MONA_WAIT_VM(0);
     __builtin_amdgcn_s_barrier();
     issue(3, 3);
-    MONA_STAMP(1);
     fill(IC<0>{}, IC<0>{}, IC<0>{});
     int kt = 0;
     // first pass of the ring: chunk 3 is in flight alone, then the steady pattern sets in
@@ -1058,7 +1060,6 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
     }
     step(IC<2>{}, kt + 2, IC<1>{}, IC<0>{}, IC<0>{}, IC<0>{}, IC<0>{});
     step(IC<3>{}, kt + 3, IC<0>{}, IC<0>{}, IC<0>{}, IC<0>{}, IC<0>{});
-    MONA_STAMP(2);
     // every wavefront is done with the operand stages: request the next tile's first chunks into
     // stages 0..2 now, so that they travel while this tile's epilogue runs out of stage 3
     const TileId next = tile_at(round + 1);
@@ -1072,7 +1073,6 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
     }
     if constexpr (UPD) epi.begin(t.mat, t.ti * BM + wm * WM, t.tj * BN + wn * WN, false);
     epi.run(acc, stage_f);
-    MONA_STAMP(3);
     if (!next.valid) break;
     t = next;
   }
@@ -1191,30 +1191,6 @@ hipError_t launch_bf16(const GemmArgs& a, bool tp, bool tq, int grid, hipStream_
 
 }  // namespace
 
-static void dma_debug_report(const GemmArgs& a, bool transP, bool transQ, int grid, long long total) {
-#ifdef MONA_TIMING
-  (void)hipDeviceSynchronize();
-  static unsigned long long host[8 * 65536];
-  const int nb = grid < 65536 ? grid : 65536;
-  (void)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_timing), sizeof(unsigned long long) * 8 * nb);
-  double s41 = 0, s12 = 0, s23 = 0, whole = 0, rounds = 0;
-  int n = 0;
-  for (int b = 0; b < nb && b < (int)total; ++b) {
-    const unsigned long long* q = host + 8 * b;
-    if (q[3] <= q[0] || q[5] == 0) continue;
-    s41 += (double)(q[1] - q[4]); s12 += (double)(q[2] - q[1]); s23 += (double)(q[3] - q[2]);
-    whole += (double)(q[3] - q[0]); rounds += (double)q[5];
-    ++n;
-  }
-  if (n)
-    fprintf(stderr, "[timing] tile %dx%d M %d N %d K %d sym %d tP %d tQ %d epi %d tiles %lld: prime %.0f  loop %.0f (%.1f/step)  epilogue %.0f  per-tile %.0f rounds %.1f\n",
-            a.tile_m, a.tile_n, a.M, a.N, a.K, a.symmetric, (int)transP, (int)transQ, a.epilogue, total, s41 / n, s12 / n,
-            s12 / n / (a.K / 32), s23 / n, whole / rounds, rounds / n);
-#else
-  (void)a; (void)transP; (void)transQ; (void)grid; (void)total;
-#endif
-}
-
 hipError_t launch_ns_gemm(const GemmArgs& a, int tile, bool transP, bool transQ, bool f32, hipStream_t s) {
   const long long total = (long long)a.tiles_per_mat * a.count;
   if (total <= 0) return hipSuccess;
@@ -1238,19 +1214,27 @@ hipError_t launch_ns_gemm(const GemmArgs& a, int tile, bool transP, bool transQ,
     }();
     const int pgrid = grid < num_cus ? grid : num_cus;
 #define MONA_LAUNCH_DMA(TP_, TQ_, UPD_, E_)                                                                        \
-  hipLaunchKernelGGL((ns_gemm_bf16_dma_kernel<256, 256, 2, 4, 4, 1, TP_, TQ_, UPD_, E_>), dim3(pgrid), dim3(512), 0, s, a)
+  hipLaunchKernelGGL((ns_gemm_bf16_dma_kernel<256, 256, 2, 4, 4, 1, TP_, TQ_, UPD_, E_, false>), dim3(pgrid), dim3(512), 0, s, a)
     const bool upd = a.epilogue == EPI_UPDATE, has_e = a.E != nullptr;
-    // the plan uses: Gram (no E; both operands row-major, or both K-major for a tall matrix); poly and the
-    // apply of a wide matrix (E, both operands K-major); the apply of a tall matrix and every apply that
-    // carries the update (E, P row-major, Q K-major)
-    if (!transP && !transQ && !upd && !has_e) MONA_LAUNCH_DMA(false, false, false, false);
+    // the plan uses: Gram and the products of two commuting symmetric matrices (no E; both operands row-major,
+    // or both K-major); poly and the apply of a wide matrix (E, both operands K-major); the apply of a tall
+    // matrix (P row-major, Q K-major; with E in the literal schedule, without in the fused one); and the
+    // apply that carries the update (P row-major: a K-major P leaves it no registers; with or without E)
+    if (a.diag != 0.0f) {
+      // only the poly launches of the fused schedule (symmetric, E, both operands K-major) add a diagonal term
+      if (!(transP && transQ && !upd && has_e && a.symmetric)) return hipErrorInvalidValue;
+      hipLaunchKernelGGL((ns_gemm_bf16_dma_kernel<256, 256, 2, 4, 4, 1, true, true, false, true, true>), dim3(pgrid),
+                         dim3(512), 0, s, a);
+    }
+    else if (!transP && !transQ && !upd && !has_e) MONA_LAUNCH_DMA(false, false, false, false);
     else if (transP && transQ && !upd && !has_e) MONA_LAUNCH_DMA(true, true, false, false);
     else if (transP && transQ && !upd && has_e) MONA_LAUNCH_DMA(true, true, false, true);
     else if (!transP && transQ && !upd && has_e) MONA_LAUNCH_DMA(false, true, false, true);
+    else if (!transP && transQ && !upd && !has_e) MONA_LAUNCH_DMA(false, true, false, false);
     else if (!transP && transQ && upd && has_e) MONA_LAUNCH_DMA(false, true, true, true);
+    else if (!transP && transQ && upd && !has_e) MONA_LAUNCH_DMA(false, true, true, false);
     else return hipErrorInvalidValue;
 #undef MONA_LAUNCH_DMA
-    dma_debug_report(a, transP, transQ, pgrid, total);
     return hipGetLastError();
   }
   if (tile == 128) return launch_bf16<128, 128>(a, transP, transQ, grid, s);

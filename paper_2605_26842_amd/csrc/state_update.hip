@@ -18,23 +18,8 @@ typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
 
 // The state is streamed: every array is read once and written once per step and is not touched
 // again before the next step, so the accesses are marked non-temporal.
-#ifndef MONA_EW_NT
-#define MONA_EW_NT 1
-#endif
-template <typename V> __device__ __forceinline__ V stream_load(const V* p) {
-#if MONA_EW_NT
-  return __builtin_nontemporal_load(p);
-#else
-  return *p;
-#endif
-}
-template <typename V> __device__ __forceinline__ void stream_store(V* p, V v) {
-#if MONA_EW_NT
-  __builtin_nontemporal_store(v, p);
-#else
-  *p = v;
-#endif
-}
+template <typename V> __device__ __forceinline__ V stream_load(const V* p) { return __builtin_nontemporal_load(p); }
+template <typename V> __device__ __forceinline__ void stream_store(V* p, V v) { __builtin_nontemporal_store(v, p); }
 __device__ __forceinline__ f32x4 load4(const float* p) { return stream_load(reinterpret_cast<const f32x4*>(p)); }
 __device__ __forceinline__ f32x4 load4(const bf16_t* p) {
   bf16x4 v = stream_load(reinterpret_cast<const bf16x4*>(p));
@@ -68,13 +53,16 @@ __device__ __forceinline__ float mona_element(float g, float gp, float& a, float
   return c.mu * m + gt;                              // M_k = mu M_{k-1} + Gt_k
 }
 
-__device__ __forceinline__ float block_sum(float v, float* red) {
+// The squares are summed in double: M_ij^2 leaves the fp32 range once |M_ij| is below about 1e-19 or above
+// 1e19 (a matrix that has received no gradient for a few hundred steps decays to such values), and the
+// norm must still come out right there.  The kernel is bound by HBM; the fp64 operations are free.
+__device__ __forceinline__ double block_sum(double v, double* red) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);   // within the wavefront
   const int wave = threadIdx.x >> 6;
   if ((threadIdx.x & 63) == 0) red[wave] = v;                            // then across wavefronts in LDS
   __syncthreads();
-  float t = 0.0f;
+  double t = 0.0;
   if (threadIdx.x == 0) {
 #pragma unroll
     for (int w = 0; w < kEwThreads / 64; ++w) t += red[w];
@@ -98,8 +86,8 @@ enum StateMode : int { MODE_MUON = 0, MODE_TWO_BUFFER = 1, MODE_ONE_BUFFER = 2 }
 template <typename GT, typename ST, int MODE>
 __global__ __launch_bounds__(kEwThreads) void state_update_kernel(
     const MatStatic* __restrict__ stat, const MatDynamic* __restrict__ dyn,
-    const BlockWork* __restrict__ work, float* __restrict__ partials, Coef c) {
-  __shared__ float red[kEwThreads / 64];
+    const BlockWork* __restrict__ work, double* __restrict__ partials, Coef c) {
+  __shared__ double red[kEwThreads / 64];
   const BlockWork bw = work[blockIdx.x];
   const MatStatic ms = stat[bw.mat];
   const GT* __restrict__ g = static_cast<const GT*>(dyn[bw.mat].g);
@@ -116,7 +104,7 @@ __global__ __launch_bounds__(kEwThreads) void state_update_kernel(
   const int base = bw.chunk * kEwChunk;
   const int count = min(kEwChunk, total - base);
   const int n = ms.n, ldx = ms.ldx;
-  float ss = 0.0f;
+  double ss = 0.0;
 
   if ((n & 3) == 0) {
     // rows are a multiple of 4 elements: 4-element groups never straddle a row
@@ -154,7 +142,7 @@ __global__ __launch_bounds__(kEwThreads) void state_update_kernel(
           }
           const f32x4 a = {a4[0], a4[1], a4[2], a4[3]};
           const f32x4 mnew = {n4[0], n4[1], n4[2], n4[3]};
-          ss += mnew.x * mnew.x + mnew.y * mnew.y + mnew.z * mnew.z + mnew.w * mnew.w;
+          ss += (double)mnew.x * mnew.x + (double)mnew.y * mnew.y + (double)mnew.z * mnew.z + (double)mnew.w * mnew.w;
           if constexpr (MODE == MODE_TWO_BUFFER) store4(gp + idx[b], vg[b]);   // G_{k-1} <- G_k
           if constexpr (MODE != MODE_MUON) store4(ac + idx[b], a);              // A_k, or C_{k+1}
           store4(mo + idx[b], mnew);
@@ -181,45 +169,85 @@ __global__ __launch_bounds__(kEwThreads) void state_update_kernel(
       } else {
         mnew = c.mu * mo[id] + gv;
       }
-      ss += mnew * mnew;
+      ss += (double)mnew * mnew;
       mo[id] = mnew;
       const int64_t xo = (int64_t)(id / n) * ldx + (id % n);
       if (xf32) xf[xo] = mnew; else xh[xo] = (bf16_t)mnew;
     }
   }
-  const float t = block_sum(ss, red);
+  const double t = block_sum(ss, red);
   if (threadIdx.x == 0) partials[blockIdx.x] = t;
 }
 
 // ||M||_F per matrix from the per-block partial sums, added in a fixed order in fp64 so the
 // result does not depend on scheduling.  One wavefront per matrix.
+//
+// The products that follow accumulate the unscaled working copy in fp32 and apply 1 / ||M||_F^2 afterwards,
+// which is exact only while the squares stay inside the fp32 range.  A norm outside [2^-40, 2^40] therefore
+// sets MONA_STATUS_RESCALED: rescue_kernel then rewrites that matrix's working copy as M 2^e with
+// ||M 2^e||_F in [1, 2), and the scale stored here is the one that belongs to the rewritten copy (a power
+// of two moves no bit of any product, so the result is the one an unlimited exponent range would give).
+constexpr double kNormLo = 9.094947017729282e-13;   // 2^-40
+constexpr double kNormHi = 1099511627776.0;         // 2^40
 __global__ __launch_bounds__(64) void norm_finalize_kernel(const MatStatic* __restrict__ stat,
-                                                           const float* __restrict__ partials,
+                                                           const double* __restrict__ partials,
                                                            MatScale* __restrict__ scales, float eps) {
   const int mat = blockIdx.x;
   const int first = stat[mat].first_block, nb = stat[mat].num_blocks;
   double s = 0.0;
-  for (int i = threadIdx.x; i < nb; i += 64) s += (double)partials[first + i];
+  for (int i = threadIdx.x; i < nb; i += 64) s += partials[first + i];
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
   if (threadIdx.x == 0) {
-    const float norm = (float)sqrt(s);
-    const float den = norm + eps;
+    const double norm = sqrt(s);
+    const double den = norm + (double)eps;
     MatScale r;
-    r.norm = norm;
+    r.norm = (float)fmin(norm, 3.402823466e38);
     r.status = 0u;
-    const bool finite = (den == den) && (den <= 3.402823466e38f);
+    r.xexp = 0;
+    const bool finite = (s == s) && (s <= 1.7e308);
     if (!finite) {
+      r.norm = (float)norm;
       r.inv = 0.0f;
       r.status = 2u;
-    } else if (den <= 0.0f) {
+    } else if (den <= 0.0) {
       r.inv = 0.0f;
       r.status = 1u;
+    } else if (norm == 0.0 || (norm >= kNormLo && norm <= kNormHi)) {
+      r.inv = 1.0f / ((float)norm + eps);
     } else {
-      r.inv = 1.0f / den;
+      r.xexp = -ilogb(norm);
+      r.inv = (float)ldexp(1.0 / den, -r.xexp);
+      r.status = 4u;
     }
     r.inv2 = r.inv * r.inv;
     scales[mat] = r;
+  }
+}
+
+// Repairs the working copies of the (rare) matrices norm_finalize_kernel has flagged, before any product
+// reads them: a matrix with a non-finite norm gets an all-zero copy (its products then stay zero, so no
+// NaN ever reaches the zero padding the Gram matrices rely on; its parameter is left alone anyway), and a
+// matrix whose norm lies outside the safe window gets the copy M 2^e.  Every block scans the flags and
+// leaves at once when none is set.
+__global__ __launch_bounds__(256) void rescue_kernel(const MatStatic* __restrict__ stat,
+                                                     const MatScale* __restrict__ scales, int count) {
+  int any = 0;
+  for (int i = threadIdx.x; i < count; i += 256) any |= (scales[i].status & 6u) != 0;
+  if (!__syncthreads_or(any)) return;
+  for (int mat = 0; mat < count; ++mat) {
+    const uint32_t st = scales[mat].status;
+    if (!(st & 6u)) continue;
+    const MatStatic ms = stat[mat];
+    const int e = scales[mat].xexp;
+    const int64_t total = (int64_t)ms.m * ms.n;
+    bf16_t* __restrict__ xh = static_cast<bf16_t*>(ms.x);
+    float* __restrict__ xf = static_cast<float*>(ms.x);
+    for (int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x; id < total; id += (int64_t)gridDim.x * 256) {
+      const int64_t xo = (id / ms.n) * ms.ldx + (id % ms.n);
+      const float v = (st & 2u) ? 0.0f : ldexpf(ms.mom[id], e);
+      if (ms.x_f32) xf[xo] = v; else xh[xo] = (bf16_t)v;
+    }
   }
 }
 
@@ -265,14 +293,14 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(uint4* __restrict__ p, s
 }
 
 template <typename GT, typename ST, int MODE>
-hipError_t launch_su(const MatStatic* stat, const MatDynamic* dyn, const BlockWork* work, float* partials,
+hipError_t launch_su(const MatStatic* stat, const MatDynamic* dyn, const BlockWork* work, double* partials,
                      int num_blocks, Coef c, hipStream_t s) {
   hipLaunchKernelGGL((state_update_kernel<GT, ST, MODE>), dim3(num_blocks), dim3(kEwThreads), 0, s, stat, dyn,
                      work, partials, c);
   return hipGetLastError();
 }
 template <int MODE>
-hipError_t launch_su_mode(const MatStatic* stat, const MatDynamic* dyn, const BlockWork* work, float* partials,
+hipError_t launch_su_mode(const MatStatic* stat, const MatDynamic* dyn, const BlockWork* work, double* partials,
                           int num_blocks, int g_bf16, int state_bf16, Coef c, hipStream_t s) {
   switch ((g_bf16 ? 2 : 0) | (state_bf16 ? 1 : 0)) {
     case 0: return launch_su<float, float, MODE>(stat, dyn, work, partials, num_blocks, c, s);
@@ -287,7 +315,7 @@ hipError_t launch_su_mode(const MatStatic* stat, const MatDynamic* dyn, const Bl
 // The gradient dtype may differ between matrices: the host orders the work table by gradient
 // dtype and launches each dtype's range of blocks separately.
 hipError_t launch_state_update(const MatStatic* stat, const MatDynamic* dyn, const BlockWork* work,
-                               float* partials, int num_blocks, int g_bf16, int state_bf16, int one_buffer,
+                               double* partials, int num_blocks, int g_bf16, int state_bf16, int one_buffer,
                                float mu, float beta_a, float alpha, int use_prev, hipStream_t s) {
   if (num_blocks <= 0) return hipSuccess;
   Coef c;
@@ -307,10 +335,13 @@ hipError_t launch_state_update(const MatStatic* stat, const MatDynamic* dyn, con
   return launch_su_mode<MODE_TWO_BUFFER>(stat, dyn, work, partials, num_blocks, g_bf16, state_bf16, c, s);
 }
 
-hipError_t launch_norm_finalize(const MatStatic* stat, const float* partials, MatScale* scales, int count,
+hipError_t launch_norm_finalize(const MatStatic* stat, const double* partials, MatScale* scales, int count,
                                 float eps, hipStream_t s) {
   if (count <= 0) return hipSuccess;
   hipLaunchKernelGGL(norm_finalize_kernel, dim3(count), dim3(64), 0, s, stat, partials, scales, eps);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(rescue_kernel, dim3(1024), dim3(256), 0, s, stat, scales, count);
   return hipGetLastError();
 }
 

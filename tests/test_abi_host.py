@@ -61,9 +61,23 @@ def test_state_size_accounts_for_state_and_workspace():
     assert rag >= 100 * 300 * 12 + 2 * 128 * 384 * 2 + 2 * 128 * 128 * 2
     # the large MoE layer of the benchmark: ~45 GB of state, ~60 GB in all
     layer = shapes(*([(4096, 4096)] * 4 + [(4096, 1536)] * 256 + [(1536, 4096)] * 128))
-    total = B.mona_state_size(layer, 388)
     elems = 4 * 4096 * 4096 + 384 * 4096 * 1536
-    assert elems * 12 < total < elems * 12 * 1.6
+    literal = B.mona_state_size(layer, 388, B.mona_options(ns_schedule=B.MONA_NS_SCHEDULE_LITERAL))
+    assert elems * 12 < literal < elems * 12 * 1.6
+    # the fused Newton-Schulz schedule (the automatic choice for the 384 expert matrices: long side 4096,
+    # short side 1536) keeps six p x p working matrices per matrix instead of two
+    total = B.mona_state_size(layer, 388)
+    assert total - literal == 384 * 4 * 1536 * 1536 * 2
+    fused = B.mona_state_size(layer, 388, B.mona_options(ns_schedule=B.MONA_NS_SCHEDULE_FUSED))
+    assert fused - total == 4 * 4 * 4096 * 4096 * 2
+    # the automatic choice leaves 1024 x 2048 and 512 x 4096 literal and fuses 2048 x 8192
+    for shape, is_fused in (((1024, 2048), False), ((512, 4096), False), ((2048, 8192), True), ((8192, 2048), True),
+                            ((1536, 1536), False)):
+        auto = B.mona_state_size(shapes(shape), 1)
+        lit = B.mona_state_size(shapes(shape), 1, B.mona_options(ns_schedule=B.MONA_NS_SCHEDULE_LITERAL))
+        assert (auto > lit) == is_fused, shape
+    with pytest.raises(B.MonaError):
+        B.mona_state_size(layer, 388, B.mona_options(ns_schedule=3))
 
 
 def rc_of(fn, *args):
@@ -121,7 +135,7 @@ def test_bad_arguments_are_rejected_on_the_host():
     rc, msg = rc_of(lib.mona_state_size, shapes((4, 4)), 1, C.byref(B.mona_options(0, 0, 3)), C.byref(out))
     assert rc == B.MONA_EINVAL and "accel_form" in msg
     rc, msg = rc_of(lib.mona_state_size, shapes((4, 4)), 1,
-                    C.byref(B.mona_options(0, 0, 0, 0, (C.c_int32 * 4)(0, 0, 1, 0))), C.byref(out))
+                    C.byref(B.mona_options(0, 0, 0, 0, 0, (C.c_int32 * 3)(0, 1, 0))), C.byref(out))
     assert rc == B.MONA_EINVAL and "reserved" in msg
     rc, msg = rc_of(lib.mona_state_size, shapes((4, 4)), 1, C.byref(B.mona_options(0, 0, 0, 9)), C.byref(out))
     assert rc == B.MONA_EINVAL and "max_streams" in msg

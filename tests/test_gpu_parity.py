@@ -602,10 +602,15 @@ def test_profiling_and_plan_reports():
     dev = "cuda:0"
     weights = [wl.draw_weight(s, 500 + i, torch.bfloat16, dev) for i, s in enumerate(shapes)]
     grads = [wl.GradientStream(s, 600 + i, dev).next() for i, s in enumerate(shapes)]
-    opt = B.MonaOptimizer(weights)
     hp = wl.HParams()
+    # the fused schedule: per group Gram + 9 p x p products + apply for
+    # the chunk of three iterations, Gram + 5 + apply for the chunk of two; fewer flop than the literal one
+    fused = B.MonaOptimizer(weights, ns_schedule=B.MONA_NS_SCHEDULE_FUSED).plan_info(hp.ns_steps)
+    assert fused["ns_launches"] == 2 * (11 + 7)
+    opt = B.MonaOptimizer(weights, ns_schedule=B.MONA_NS_SCHEDULE_LITERAL)
     plan = opt.plan_info(hp.ns_steps)
     assert plan["ns_launches"] == 2 * 3 * hp.ns_steps            # two shape groups
+    assert fused["ns_flops_issued"] < plan["ns_flops_issued"]
     n_elem = sum(a * b for a, b in shapes)
     assert plan["elementwise_bytes"] == n_elem * 30
     sym = sum(hp.ns_steps * (3.0 * min(s) ** 2 * max(s) + min(s) ** 3) for s in shapes)
