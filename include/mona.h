@@ -180,6 +180,26 @@ int mona_step(mona_state* st, const mona_matrix* mats, int32_t count,
 int mona_step_streaming(mona_state* st, const mona_matrix* mats, void* const* slots, int32_t count,
                         const mona_hparams* hp, void* stream);
 
+/* For callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  One step of Alg. 1 for ONE matrix whose state arrays the caller keeps, with no state
+ * handle and no arena: the workspace mona_step finds in the arena (working copies, p x p matrices, partial
+ * sums, tables) is a static device array of MONA_NOALLOC_SCRATCH_BYTES inside the library, which every GPU
+ * the library runs on holds until the process ends.  The call allocates nothing (no hipMalloc, no pinned
+ * host memory, no events or streams), copies nothing from host memory and enqueues only kernels on `stream`.
+ *   mat     HOST    one descriptor; w and g DEVICE as for mona_step
+ *   opts    HOST    NULL = all zero; accel_form must be MONA_ACCEL_TWO_BUFFER
+ *   g_prev  DEVICE  G_{k-1}: m x n of opts->state_dtype, in/out (all zero before the first step)
+ *   acc     DEVICE  A_{k-1} in, A_k out: m x n of opts->state_dtype
+ *   mom     DEVICE  M_{k-1} in, M_k out: m x n fp32        (all three 16-byte aligned, caller-owned)
+ *   k       number of steps this matrix has taken before (only MONA_FLAG_FIRST_DIFF_ZERO looks at it)
+ * Results are those of mona_step on a state that holds this one matrix, bit for bit.
+ * MONA_ENOMEM if the matrix needs more workspace than the static array holds (roughly: padded m x n up to
+ * 2 M elements with a short side up to 1024).  All calls on one GPU share that GPU's array: calls that
+ * overlap in time on one GPU (different streams, different threads) race; order them. */
+#define MONA_NOALLOC_SCRATCH_BYTES ((size_t)32 << 20)
+int mona_step_noalloc(const mona_matrix* mat, const mona_options* opts, void* g_prev, void* acc, void* mom,
+                      const mona_hparams* hp, int64_t k, void* stream);
+
 /* Release host bookkeeping (waits for the state's pinned tables to be idle).  The arena
  * is not touched. */
 int mona_free_state(mona_state* st);

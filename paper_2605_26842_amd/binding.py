@@ -26,7 +26,7 @@ MONA_STATUS_ZERO_NORM, MONA_STATUS_NONFINITE, MONA_STATUS_RESCALED = 0x1, 0x2, 0
 MONA_NS_SCHEDULE_AUTO, MONA_NS_SCHEDULE_LITERAL, MONA_NS_SCHEDULE_FUSED = 0, 1, 2
 
 EXPORTED = (
-    "mona_state_size", "mona_init_state", "mona_step", "mona_step_streaming", "mona_free_state",
+    "mona_state_size", "mona_init_state", "mona_step", "mona_step_streaming", "mona_step_noalloc", "mona_free_state",
     "mona_state_view",
     "mona_state_export_size", "mona_state_export", "mona_state_import", "mona_state_step_count",
     "mona_state_status", "mona_set_profiling", "mona_last_step_times", "mona_mean_step_times", "mona_last_step_launches",
@@ -101,6 +101,7 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.mona_init_state.argtypes = [P(mona_matrix), i32, P(mona_options), vp, sz, vp, P(vp)]
     lib.mona_step.argtypes = [vp, P(mona_matrix), i32, P(mona_hparams), vp]
     lib.mona_step_streaming.argtypes = [vp, P(mona_matrix), P(vp), i32, P(mona_hparams), vp]
+    lib.mona_step_noalloc.argtypes = [P(mona_matrix), P(mona_options), vp, vp, vp, P(mona_hparams), i64, vp]
     lib.mona_free_state.argtypes = [vp]
     lib.mona_state_view.argtypes = [vp, i32, i32, P(mona_view)]
     lib.mona_state_export_size.argtypes = [vp, P(sz)]
@@ -192,6 +193,13 @@ def mona_step(state: int, mats, count: int, hp: mona_hparams, stream: int) -> No
 
 def mona_step_streaming(state: int, mats, slots, count: int, hp: mona_hparams, stream: int) -> None:
     _check(load_library().mona_step_streaming(state, mats, slots, count, C.byref(hp), stream))
+
+
+def mona_step_noalloc(mat, opts: Optional[mona_options], g_prev: int, acc: int, mom: int, hp: mona_hparams, k: int,
+                      stream: int) -> None:
+    """One step of one matrix with caller-kept state arrays (device addresses) and the library's static workspace."""
+    _check(load_library().mona_step_noalloc(mat, C.byref(opts) if opts is not None else None, g_prev, acc, mom,
+                                            C.byref(hp), k, stream))
 
 
 def mona_free_state(state: int) -> None:

@@ -11,6 +11,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <map>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -961,6 +962,93 @@ int step_impl(mona_state* st, const mona_matrix* mats, void* const* slots, int32
 }
 
 }  // namespace
+
+// ---- the entry point that allocates nothing -------------------------------------------------------------
+namespace {
+
+// Workspace of mona_step_noalloc: what mona_step keeps in the caller's arena beyond the state arrays (the
+// working copies X, the p x p matrices, per-block partial sums, scales and the small tables), here in a
+// static device array.  Every GPU the library runs on holds its own copy, at its own address, until the
+// process ends.
+constexpr size_t kScratchBytes = MONA_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each device, looked up once
+
+// Device address of the scratch array on the current device.  In host code the array's name is only a
+// handle for this lookup, never an address to hand to a kernel.
+int scratch_on_current_device(char** out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(MONA_EUNSUPPORTED, "device ordinal %d is beyond %d", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(MONA_EHIP, "hipGetSymbolAddress returned a null address for the scratch array");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = static_cast<char*>(g_scratch_ptr[dev]);
+  return MONA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int mona_step_noalloc(const mona_matrix* mat, const mona_options* opts, void* g_prev, void* acc, void* mom,
+                      const mona_hparams* hp, int64_t k, void* stream) {
+  g_err.clear();
+  int rc = check_mats(mat, 1, true);
+  if (rc) return rc;
+  rc = check_hparams(hp);
+  if (rc) return rc;
+  mona_options o;
+  rc = check_opts(opts, &o);
+  if (rc) return rc;
+  if (o.accel_form != MONA_ACCEL_TWO_BUFFER)
+    return fail(MONA_EUNSUPPORTED, "mona_step_noalloc takes the state arrays of Alg. 1 (MONA_ACCEL_TWO_BUFFER) only");
+  if (k < 0) return fail(MONA_EINVAL, "k must be >= 0");
+  if (!g_prev || !acc || !mom) return fail(MONA_EINVAL, "g_prev, acc and mom must not be NULL");
+  if (((uintptr_t)g_prev & 15) || ((uintptr_t)acc & 15) || ((uintptr_t)mom & 15))
+    return fail(MONA_EINVAL, "g_prev, acc and mom must be 16-byte aligned");
+  // the same plan a one-matrix mona_init_state would build, laid out over the scratch array
+  mona_state st;
+  build_layout(mat, 1, o, true, st.L);
+  const Layout& L = st.L;
+  if (L.total > kScratchBytes)
+    return fail(MONA_ENOMEM, "a %d x %d matrix needs %zu bytes of workspace; the static scratch of mona_step_noalloc "
+                "holds %zu (use mona_step with an arena for larger matrices)", mat->m, mat->n, L.total, kScratchBytes);
+  char* base = nullptr;
+  rc = scratch_on_current_device(&base);
+  if (rc) return rc;
+  st.opt = o;
+  st.mats.assign(mat, mat + 1);
+  st.arena = base;
+  st.k = k;
+  st.lane_of_group.assign(L.groups.size(), 0);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // The array keeps what the last call left in it: the padding of the working matrices and the scales must
+  // start from zero (a fill kernel, not a memset: the call may be under graph capture).
+  HIP_TRY(launch_fill_zero(base + L.work_begin, L.work_bytes, s));
+  HIP_TRY(launch_fill_zero(base + L.scales_off, align_up(sizeof(MatScale)), s));
+  MatStatic ms;
+  void* o_ptr = nullptr;
+  fill_static(L, *mat, 0, base, g_prev, acc, mom, ms, o_ptr);
+  MatDynamic md;
+  md.w = mat->w; md.g = mat->g; md.slot = nullptr;
+  HIP_TRY(launch_single_tables(ms, md, o_ptr, st.at<MatStatic>(L.stat_off), st.at<MatDynamic>(L.dyn_off),
+                               st.at<void*>(L.optr_off), st.at<BlockWork>(L.blocks_off), (int)L.blocks.size(),
+                               reinterpret_cast<int32_t*>(base + L.groups[0].members_off), s));
+  rc = enqueue_step(&st, hp, s);
+  if (rc) return rc;
+  note_unstable_alpha(hp);
+  return MONA_OK;
+}
+
+}  // extern "C"
 
 extern "C" {
 

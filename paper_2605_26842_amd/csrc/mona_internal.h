@@ -93,6 +93,10 @@ hipError_t launch_state_update(const MatStatic* stat, const MatDynamic* dyn, con
 // norm_finalize_kernel, then rescue_kernel (repairs the working copies of flagged matrices)
 hipError_t launch_norm_finalize(const MatStatic* stat, const double* partials, MatScale* scales,
                                 int count, float eps, hipStream_t s);
+// tables of a one-matrix state written by a kernel from its arguments (no host copy)
+hipError_t launch_single_tables(const MatStatic& ms, const MatDynamic& md, void* o_ptr, MatStatic* stat,
+                                MatDynamic* dyn, void** o_ptrs, BlockWork* work, int num_blocks, int32_t* members,
+                                hipStream_t s);
 hipError_t launch_plain_update(const MatStatic* stat, const MatDynamic* dyn, const MatScale* scales,
                                const BlockWork* work, int num_blocks, void* const* o_ptrs, float lr, float wd,
                                float gamma_coeff, int store_o, hipStream_t s);

@@ -251,6 +251,16 @@ __global__ __launch_bounds__(256) void rescue_kernel(const MatStatic* __restrict
   }
 }
 
+// Tables of a state that holds ONE matrix, written on the device from kernel arguments (for the entry
+// point that may neither allocate nor copy from host memory).
+__global__ __launch_bounds__(256) void single_tables_kernel(MatStatic ms, MatDynamic md, void* o_ptr, MatStatic* stat,
+                                                            MatDynamic* dyn, void** o_ptrs, BlockWork* work,
+                                                            int num_blocks, int32_t* members) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i == 0) { stat[0] = ms; dyn[0] = md; o_ptrs[0] = o_ptr; members[0] = 0; }
+  for (int b = i; b < num_blocks; b += gridDim.x * 256) work[b] = BlockWork{0, b};
+}
+
 // O = X_0 and the parameter update when no Newton-Schulz iteration is requested (T = 0),
 // W <- (1 - eta lambda) W - eta gamma O   (Eq. muon_update).
 template <typename WT>
@@ -342,6 +352,15 @@ hipError_t launch_norm_finalize(const MatStatic* stat, const double* partials, M
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(rescue_kernel, dim3(1024), dim3(256), 0, s, stat, scales, count);
+  return hipGetLastError();
+}
+
+hipError_t launch_single_tables(const MatStatic& ms, const MatDynamic& md, void* o_ptr, MatStatic* stat,
+                                MatDynamic* dyn, void** o_ptrs, BlockWork* work, int num_blocks, int32_t* members,
+                                hipStream_t s) {
+  const int blocks = num_blocks > 256 * 64 ? 64 : (num_blocks + 255) / 256;
+  hipLaunchKernelGGL(single_tables_kernel, dim3(blocks > 0 ? blocks : 1), dim3(256), 0, s, ms, md, o_ptr, stat, dyn,
+                     o_ptrs, work, num_blocks, members);
   return hipGetLastError();
 }
 
