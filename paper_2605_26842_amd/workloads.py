@@ -225,6 +225,21 @@ class GradientStream:
         return g.clone()
 
 
+    def advance(self, g: torch.Tensor) -> torch.Tensor:
+        """The next gradient written over the previous one: `g` must be the tensor the last call
+        returned or filled (any fp32 tensor of the stream's shape at the first call).  For workloads
+        whose gradients are too large to keep twice.  Draws the same z_k as `next`; the AR(1)
+        combination is rounded in a different order, so use one of the two consistently."""
+        z = torch.empty(self.shape, dtype=torch.float32, device=self.device)
+        z.normal_(0.0, 1.0, generator=self.gen)
+        if self.prev is None:
+            g.copy_(z.mul_(self.sigma))
+        else:
+            g.mul_(self.rho).add_(z, alpha=math.sqrt(1.0 - self.rho * self.rho) * self.sigma)
+        self.prev = g
+        return g
+
+
 def make_inputs(workload: Workload, workload_index: int = 0,
                 device: torch.device | str = "cpu",
                 steps: Optional[int] = None,

@@ -130,28 +130,39 @@ def check_history(weights, grads_per_step, hp, history, watch, ns_tol, state_tol
             worst["ns"] = max(worst["ns"], e)
             assert e <= ns_tol, f"{tag}: O rel Frobenius err {e:.3e} > {ns_tol}"
             bf16_param = weights[i].dtype == torch.bfloat16
-            want = expected_update(s.W_before, r["O"], hp, False)       # unrounded float64
-            dW_ref = want - s.W_before
-            dW = s.W - s.W_before
-            e = rel_fro(dW, dW_ref)
-            worst["upd"] = max(worst["upd"], e)
-            if bf16_param:
-                # the same figure with the rounding of the stored parameter made part of the reference: reported
-                # only (two independent roundings of values that differ by more than an ulp count twice there)
-                e_r = rel_fro(dW, orc.round_to_bf16(want) - s.W_before)
-                worst["upd_vs_rounded_ref"] = max(worst.get("upd_vs_rounded_ref", 0.0), e_r)
-                # the update arithmetic itself is exact given the GPU's own O: at most one
-                # bf16 ulp away from the float64 formula on a vanishing fraction of elements
-                mine = expected_update(s.W_before, s.O, hp, True)
-                diff = np.abs(mine - s.W)
-                ulp = np.maximum(np.abs(mine), 2.0 ** -126) * 2.0 ** -7
-                assert (diff <= ulp).all(), f"{tag}: bf16 parameter more than one ulp off"
-                assert (diff > 0).mean() <= 2e-3, f"{tag}: {(diff > 0).mean():.2e} of parameters mis-rounded"
-                if ns_tol < 1e-3:
-                    # fp32-class products with a bf16 parameter: the rounding of W_{k+1} (about 1e-2 of
-                    # the update at these magnitudes) is far above the 1e-4 bound, which therefore applies
-                    # to O (above) and to the arithmetic given O (the one-ulp check just made)
-                    continue
-            # no allowance for the parameter's own rounding: the bound is on the update as stored
-            assert e <= ns_tol, f"{tag}: update rel Frobenius err {e:.3e} > {ns_tol}"
+            e = check_update(s.W_before, s.W, s.O, r["O"], hp, bf16_param, ns_tol, tag, worst)
     return worst
+
+
+def check_update(W_before, W_after, O_gpu, O_ref, hp, bf16_param, ns_tol, tag, worst):
+    """The parameter update against the oracle's (Eq. muon_update).
+
+    fp32 parameter: dW = W_{k+1} - W_k as stored, relative Frobenius error <= ns_tol.
+    bf16 parameter: W_{k+1} is stored rounded, and that rounding (half an ulp of W, whatever the update) is
+    0.7-2e-2 of dW at the benchmark's magnitudes and grows from step to step with |W| -- a property of the
+    parameter format, not of the update.  So the bound is put on the update BEFORE it is stored, which the test
+    reconstructs exactly: (1 - eta lambda) W_k - eta gamma O with the GPU's own O, in float64; and the stored
+    parameter must be that value rounded to nearest even (the kernel forms it in fp32, so a rounding boundary
+    can fall differently on a vanishing fraction of elements, never by more than one ulp).  Together the two
+    checks leave no room between "the update is within ns_tol" and "the parameter holds it".  The error of dW
+    as stored is reported, and bounded by ns_tol plus the rounding-only floor measured on the same values."""
+    want = expected_update(W_before, O_ref, hp, False)          # unrounded float64
+    dW_ref = want - W_before
+    e = rel_fro(W_after - W_before, dW_ref)
+    worst["upd"] = max(worst.get("upd", 0.0), e)
+    if not bf16_param:
+        assert e <= ns_tol, f"{tag}: update rel Frobenius err {e:.3e} > {ns_tol}"
+        return e
+    mine = expected_update(W_before, O_gpu, hp, False)
+    e_pre = rel_fro(mine - W_before, dW_ref)
+    worst["upd_before_rounding"] = max(worst.get("upd_before_rounding", 0.0), e_pre)
+    assert e_pre <= ns_tol, f"{tag}: update (before the bf16 store) rel Frobenius err {e_pre:.3e} > {ns_tol}"
+    stored = orc.round_to_bf16(mine)
+    diff = np.abs(stored - W_after)
+    ulp = np.maximum(np.abs(stored), 2.0 ** -126) * 2.0 ** -7
+    assert (diff <= ulp).all(), f"{tag}: bf16 parameter more than one ulp off"
+    assert (diff > 0).mean() <= 2e-3, f"{tag}: {(diff > 0).mean():.2e} of parameters mis-rounded"
+    floor = np.linalg.norm(orc.round_to_bf16(want) - want) / max(np.linalg.norm(dW_ref), 1e-300)
+    worst["upd_rounding_floor"] = max(worst.get("upd_rounding_floor", 0.0), floor)
+    assert e <= ns_tol + floor, f"{tag}: update as stored rel Frobenius err {e:.3e} > {ns_tol} + {floor:.2e}"
+    return e
