@@ -292,14 +292,18 @@ def main() -> int:
     ew_gbs = ew_bytes / (ew_ms * 1e-3) / 1e9 if ew_ms > 0 else 0.0
 
     # HBM bytes per launch measured with rocprofv3 counters (a committed summary, not measured here)
-    traffic_ns = traffic_ew = None
+    traffic_ns = traffic_ew = traffic_source = None
     tpath = os.path.join(ROOT, "profiles", f"traffic_{args.workload}.json")
     if os.path.exists(tpath) and args.ns_precision == 0 and args.g_dtype == "f32" and args.state_dtype == "f32" \
             and not args.muon_only and args.accel_form == "two-buffer":
         with open(tpath) as f:
             tj = json.load(f)
-        traffic_ns = tj.get("ns_gemm_bytes_per_launch")
+        # the figures belong to the launch plan they were measured on: dropped when the plan has changed since
+        if tj.get("ns_launches_per_step") == plan["ns_launches"]:
+            traffic_ns = tj.get("ns_gemm_bytes_per_launch")
         traffic_ew = tj.get("state_update_bytes_per_launch")
+        traffic_source = f"profiles/traffic_{args.workload}.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this " \
+                         "command, committed; not measured in this run)"
 
     out = {
         "metric": "MONA optimizer steps/s",
@@ -327,6 +331,7 @@ def main() -> int:
             "bound": "mfma", "achieved": ns_tflops, "peak": peak, "unit": "TFLOP/s",
             "frac": ns_tflops / peak,
             "traffic": traffic_ns,
+            "traffic_source": traffic_source,
             "flops_per_step_algorithmic": flops_sym,
             "flops_per_step_issued": plan["ns_flops_issued"],
             "flops_per_step_dense_equivalent": flops_dense,
