@@ -166,6 +166,10 @@ def main() -> int:
     ap.add_argument("--ns-schedule", default="auto", choices=["auto", "literal", "fused"],
                     help="layout of the Newton-Schulz iterations as products: literal = Gram, poly, apply per "
                          "iteration; fused = chunks of iterations advanced on the p x p side; auto = the library's choice")
+    ap.add_argument("--overlap", default="off", choices=["off", "late-group"],
+                    help="late-group: the elementwise pass of the largest shape group runs beside the products of the "
+                         "other groups on a quarter of the CUs; off (the library's default): one elementwise pass "
+                         "over everything first")
     ap.add_argument("--streams", type=int, default=0,
                     help="streams the shape groups' launch chains are spread over (0 = library default, 1 = one)")
     ap.add_argument("--graph", action="store_true",
@@ -193,6 +197,9 @@ def main() -> int:
         return bench_adamw(args)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    # everything below runs on one stream of its own (default priority), not on the null stream: the library
+    # can then run part of the elementwise pass beside the products (the null stream would serialise them)
+    torch.cuda.set_stream(torch.cuda.Stream(dev))
     workload = wl.WORKLOADS[args.workload]
     widx = list(wl.WORKLOADS).index(args.workload)
     hp = wl.HParams(flags=B.MONA_FLAG_MUON_ONLY if args.muon_only else 0, ns_steps=args.ns_steps)
@@ -218,7 +225,8 @@ def main() -> int:
         slots = [torch.zeros(s, dtype=state_dtype, device=dev) for s in shapes]
     opt = B.MonaOptimizer(weights, ns_precision=args.ns_precision, state_dtype=state_dtype, g_dtype=g_dtype,
                           accel_form=accel_form, max_streams=args.streams,
-                          ns_schedule={"auto": 0, "literal": 1, "fused": 2}[args.ns_schedule])
+                          ns_schedule={"auto": 0, "literal": 1, "fused": 2}[args.ns_schedule],
+                          overlap={"off": 0, "late-group": 1}[args.overlap])
     hpc = B.make_hparams(hp)
     plan = opt.plan_info(hp.ns_steps)
     torch.cuda.synchronize()
@@ -268,18 +276,23 @@ def main() -> int:
     # phases of these very steps (it keeps the marks of the last 32 profiled steps)
     (ew_ms, ns_ms, upd_ms, step_ms_events), n_phase = opt.mean_step_times()
 
-    launches = None
-    if args.per_launch:
-        opt.set_profiling(2)
+    # The same phases one after the other on one stream (level 2 also times every launch): in the timed steps
+    # the elementwise pass of the largest shape group may run beside the products of the other groups, on a
+    # quarter of the CUs, and is then hidden inside the Newton-Schulz interval above
+    opt.set_profiling(2)
+    for _ in range(3):
         opt.step(ring[k % len(ring)], hpc, slots)
         k += 1
+    (ew_serial_ms, ns_serial_ms, _, step_serial_ms), _ = opt.mean_step_times()
+    launches = None
+    if args.per_launch:
         launches = opt.last_step_launches()
         kinds = {0: "gram", 1: "poly", 2: "apply", 3: "sym"}
         for r in launches:
             tf = r["flops"] / (r["ms"] * 1e-3) / 1e12 if r["ms"] > 0 else 0.0
             print(f"[launch] {kinds[r['kind']]:5s} {r['m']}x{r['n']} x{r['count']} iter {r['iter']} tile {r['tile']}: "
                   f"{r['ms']:.3f} ms  {tf:.1f} TFLOP/s issued", file=sys.stderr)
-        opt.set_profiling(1)
+    opt.set_profiling(1)
 
     n_elem = workload.num_elements()
     flops_sym = workload.ns_flops_symmetric(hp.ns_steps)
@@ -289,7 +302,7 @@ def main() -> int:
     ew_bytes = plan["elementwise_bytes"]
     if args.muon_only:   # G and M read, M and the working copy written
         ew_bytes = n_elem * ((4 if args.g_dtype == "f32" else 2) + 4 + 4 + 2)
-    ew_gbs = ew_bytes / (ew_ms * 1e-3) / 1e9 if ew_ms > 0 else 0.0
+    ew_gbs = ew_bytes / (ew_serial_ms * 1e-3) / 1e9 if ew_serial_ms > 0 else 0.0
 
     # HBM bytes per launch measured with rocprofv3 counters (a committed summary, not measured here)
     traffic_ns = traffic_ew = traffic_source = None
@@ -324,7 +337,7 @@ def main() -> int:
             "state_dtype": args.state_dtype, "accel_form": args.accel_form, "ns_steps": hp.ns_steps, "ns_precision": args.ns_precision,
             "grad_ring": len(ring), "optimizer": "muon" if args.muon_only else "mona",
             "launch": "hip graph replay" if graph is not None else "eager", "streams": args.streams,
-            "ns_schedule": args.ns_schedule,
+            "ns_schedule": args.ns_schedule, "overlap": args.overlap,
         },
         "roofline": {
             "kernel": "ns_gemm (grouped Newton-Schulz products, %d launches/step)" % plan["ns_launches"],
@@ -337,14 +350,18 @@ def main() -> int:
             "flops_per_step_dense_equivalent": flops_dense,
             "ms_per_step": ns_ms,
             "avg_launch_ms": ns_ms / max(plan["ns_launches"], 1),
+            "ms_per_step_phases_in_a_row": ns_serial_ms,
         },
         "elementwise": {
             "kernel": "state_update + norm_finalize", "bound": "hbm", "achieved": ew_gbs, "peak": PEAK_HBM_GBS,
-            "unit": "GB/s", "frac": ew_gbs / PEAK_HBM_GBS, "bytes_per_step": ew_bytes, "ms_per_step": ew_ms,
+            "unit": "GB/s", "frac": ew_gbs / PEAK_HBM_GBS, "bytes_per_step": ew_bytes, "ms_per_step": ew_serial_ms,
             "traffic": traffic_ew,
+            "measured": "3 steps after the timed ones with the phases one after the other on the launch stream "
+                        "(in the timed steps part of this pass may run beside the products on a quarter of the CUs)",
         },
-        "phases_ms": {"elementwise": ew_ms, "newton_schulz": ns_ms, "separate_update": upd_ms,
-                      "step_events": step_ms_events, "steps_averaged": n_phase},
+        "phases_ms": {"elementwise_before_products": ew_ms, "newton_schulz": ns_ms, "separate_update": upd_ms,
+                      "step_events": step_ms_events, "steps_averaged": n_phase,
+                      "in_a_row": {"elementwise": ew_serial_ms, "newton_schulz": ns_serial_ms, "step": step_serial_ms}},
         "ns_tflops_dense_equivalent": flops_dense / (ns_ms * 1e-3) / 1e12 if ns_ms > 0 else 0.0,
         "ns_tflops_issued": plan["ns_flops_issued"] / (ns_ms * 1e-3) / 1e12 if ns_ms > 0 else 0.0,
     }

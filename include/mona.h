@@ -117,8 +117,23 @@ typedef struct mona_options {
                              times the short side p and for which 1 / sqrt(p) + 1 / sqrt(q) <= 0.0438 (e.g.
                              1536 x 4096, 2048 x 8192: there the fused form measured as accurate as the literal
                              one or better), literal otherwise                                          */
-  int32_t reserved[3];  /* must be 0 */
+  int32_t overlap;      /* MONA_OVERLAP_OFF (0): one elementwise pass over every matrix, then the products.
+                           MONA_OVERLAP_LATE_GROUP (1): when several large shape groups run one after the
+                           other, the elementwise pass (HBM-bound) of the one with the most elements runs on a
+                           stream confined to a quarter of the CUs, beside the matrix products (bound by the
+                           matrix units) of the other groups, which keep to the remaining CUs; its own products
+                           come last.  Results are bit-identical either way.  Takes effect only when the step
+                           is enqueued on a stream other than the null stream (HIP creates CU-masked streams
+                           as blocking ones, with which the null stream synchronises), not under stream
+                           capture, and only where the other groups' products last about as long as the
+                           slowed-down pass.  Off by default: measured on the 388-matrix MoE layer it takes
+                           3.6 % off the step but costs the products 10 % (fewer CUs, shared HBM), and on
+                           four such layers the step gets 5 % longer                                    */
+  int32_t reserved[2];  /* must be 0 */
 } mona_options;
+
+#define MONA_OVERLAP_OFF 0
+#define MONA_OVERLAP_LATE_GROUP 1
 
 #define MONA_NS_SCHEDULE_AUTO 0
 #define MONA_NS_SCHEDULE_LITERAL 1
@@ -251,7 +266,10 @@ int mona_state_status(mona_state* st, uint32_t* host_out, int32_t count, void* s
 /* Elapsed GPU time of the phases of the last mona_step, from HIP events recorded on the
  * stream the step ran on.  Enabled with mona_set_profiling(st, 1); waits for the step.
  *   ms_out HOST float[4]: elementwise state + norm, Newton-Schulz products,
- *                         update (0 when fused into the last product), whole step. */
+ *                         update (0 when fused into the last product), whole step.
+ * With a late group (mona_options.overlap) the first figure covers the pass of the other groups only and
+ * the second runs from there to the last product, the late pass hidden inside it; at level 2 everything
+ * runs in one row on the caller's stream and the figures are those of the phases one after the other. */
 int mona_set_profiling(mona_state* st, int32_t level /* 0 off, 1 phases, 2 every launch */);
 int mona_last_step_times(mona_state* st, float* ms_out);
 /* The same four figures averaged over the profiled steps since mona_set_profiling was last called (the

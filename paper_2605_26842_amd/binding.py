@@ -24,6 +24,7 @@ MONA_VIEW_G_PREV, MONA_VIEW_A, MONA_VIEW_M, MONA_VIEW_NORM, MONA_VIEW_O, MONA_VI
 MONA_ACCEL_TWO_BUFFER, MONA_ACCEL_ONE_BUFFER, MONA_ACCEL_CALLER_SLOT = 0, 1, 2
 MONA_STATUS_ZERO_NORM, MONA_STATUS_NONFINITE, MONA_STATUS_RESCALED = 0x1, 0x2, 0x4
 MONA_NS_SCHEDULE_AUTO, MONA_NS_SCHEDULE_LITERAL, MONA_NS_SCHEDULE_FUSED = 0, 1, 2
+MONA_OVERLAP_OFF, MONA_OVERLAP_LATE_GROUP = 0, 1
 
 EXPORTED = (
     "mona_state_size", "mona_init_state", "mona_step", "mona_step_streaming", "mona_step_noalloc", "mona_free_state",
@@ -61,7 +62,8 @@ class mona_hparams(C.Structure):
 
 class mona_options(C.Structure):
     _fields_ = [("ns_precision", C.c_int32), ("state_dtype", C.c_int32), ("accel_form", C.c_int32),
-                ("max_streams", C.c_int32), ("ns_schedule", C.c_int32), ("reserved", C.c_int32 * 3)]
+                ("max_streams", C.c_int32), ("ns_schedule", C.c_int32), ("overlap", C.c_int32),
+                ("reserved", C.c_int32 * 2)]
 
 
 class mona_view(C.Structure):
@@ -218,7 +220,7 @@ class MonaOptimizer:
     def __init__(self, weights: Sequence[torch.Tensor], ns_precision: int = 0,
                  state_dtype: torch.dtype = torch.float32, g_dtype: torch.dtype = torch.float32,
                  accel_form: int = MONA_ACCEL_TWO_BUFFER, max_streams: int = 0,
-                 ns_schedule: int = MONA_NS_SCHEDULE_AUTO):
+                 ns_schedule: int = MONA_NS_SCHEDULE_AUTO, overlap: int = MONA_OVERLAP_OFF):
         if not weights:
             raise ValueError("need at least one matrix")
         self.lib = load_library()
@@ -229,7 +231,7 @@ class MonaOptimizer:
         self.count = len(self.weights)
         self.g_dtype = g_dtype
         self.opts = mona_options(ns_precision, _dtype_code(state_dtype), accel_form, max_streams, ns_schedule,
-                                 (C.c_int32 * 3)())
+                                 overlap, (C.c_int32 * 2)())
         self.accel_form = accel_form
         self.ns_precision = ns_precision
         self.state_dtype = state_dtype

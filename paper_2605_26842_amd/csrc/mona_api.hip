@@ -89,7 +89,14 @@ struct Layout {
   std::vector<int> group_of, rank_in_group;
   std::vector<BlockWork> blocks;       // ordered: fp32-gradient matrices first, then bf16
   std::vector<int> first_block, num_blocks;
-  int blocks_f32g = 0;                 // number of leading blocks whose gradient is fp32
+  // The block table is ordered: early groups (fp32-gradient matrices, then bf16), then the late group (same).
+  int range_end[4] = {0, 0, 0, 0};     // ends of those four ranges of blocks
+  std::vector<int> lane_of_group;      // group index -> lane (stream) its products run on
+  int lanes = 1;
+  int late_group = -1;                 // group whose elementwise pass runs beside the products of the others
+  std::vector<int32_t> order;          // matrix indices: early matrices, then those of the late group
+  int num_early = 0;
+  size_t order_off = 0;
 };
 
 int check_mats(const mona_matrix* mats, int32_t count, bool need_ptrs) {
@@ -127,10 +134,138 @@ int check_opts(const mona_options* o, mona_options* out) {
   if (z.ns_schedule != MONA_NS_SCHEDULE_AUTO && z.ns_schedule != MONA_NS_SCHEDULE_LITERAL &&
       z.ns_schedule != MONA_NS_SCHEDULE_FUSED)
     return fail(MONA_EINVAL, "ns_schedule must be MONA_NS_SCHEDULE_AUTO, _LITERAL or _FUSED");
+  if (z.overlap != MONA_OVERLAP_OFF && z.overlap != MONA_OVERLAP_LATE_GROUP)
+    return fail(MONA_EINVAL, "overlap must be MONA_OVERLAP_OFF or MONA_OVERLAP_LATE_GROUP");
   for (int r : z.reserved)
     if (r != 0) return fail(MONA_EINVAL, "reserved option fields must be 0");
   *out = z;
   return MONA_OK;
+}
+
+constexpr int kRing = 4;
+constexpr int kProfSets = 32;
+constexpr int kDefaultLanes = 4;   // streams the shape groups of one step are spread over
+// launches of at least this many tiles keep 256 CUs busy for six rounds or more.  Measured: with the limit at
+// 512 or 768 mid-sized groups (a bank of 64 experts of 1024 x 2048) lose 4 % by waiting for each other; at
+// 3072 the two expert groups of a 128-expert layer run side by side and lose 5 % to each other's L2 traffic.
+constexpr long long kBigLaunchTiles = 1536;
+constexpr long long kChipTiles = 256;      // one tile per CU
+// CUs the late group's elementwise pass keeps to itself (a quarter of the chip): the HBM-bound pass still
+// moves 2.8 TB/s there, and the power-limited products lose 13 % on the other three quarters (measured).
+constexpr int kOverlapCuShare = 4;
+constexpr double kSlowPassBytesPerSec = 2.8e12, kProductFlopPerSec = 1.0e15, kProductSlowdown = 1.13;
+
+struct TileShape { int bm, bn; };
+
+// block tile used by one product of a group
+TileShape pick_tile(const Group& g, int kind, int count) {
+  if (g.f32 || g.gran < 256) return {128, 128};
+  long long tiles;
+  if (kind == OP_APPLY) {
+    tiles = (long long)(g.rows_pad / 256) * (g.cols_pad / 256) * count;
+  } else {
+    const long long t = g.p_pad / 256;
+    tiles = t * (t + 1) / 2 * count;
+  }
+  // too few large tiles to fill 256 CUs, unless groups running beside this one make up for it
+  if (tiles < 192 && !g.large_with_company) return {128, 128};
+  return {256, 256};
+}
+
+// tiles one product launch of a group computes
+long long launch_tiles(const Group& g, int kind, TileShape tile, int count) {
+  if (kind == OP_APPLY) return (long long)(g.rows_pad / tile.bm) * (g.cols_pad / tile.bn) * count;
+  const long long t = g.p_pad / tile.bm;
+  return t * (t + 1) / 2 * count;
+}
+
+
+// Streams and order of the step.
+//
+// Lanes.  A group whose every launch covers the chip many times over gains nothing from company (two
+// persistent kernels sharing the CUs only disturb each other's L2 reuse: measured slower), so such groups
+// stay in a row on the caller's stream; the others, sorted by work, each go to the least loaded lane.
+//
+// Late group (on request: mona_options.overlap).  The elementwise pass is bound by HBM and leaves the matrix
+// units idle; the products are bound by the matrix units (and by power) and leave HBM half idle.  When the
+// groups in the row are several, the elementwise pass of the one with the most elements is taken out of the
+// common pass and runs on a stream of its own, confined to a quarter of the CUs, beside the products of the
+// other groups, which keep to the remaining three quarters; its own products come last.  Taken only where
+// the products of the other groups last about as long as that slowed-down pass, so that it is hidden
+// completely.  Measured (388-matrix layer): the pass is hidden, but the products beside it run 10 % slower
+// (13 % from the CUs they give up, the rest from sharing HBM), which leaves 3.6 % of the step; not the default.
+void plan_lanes(Layout& L, const mona_options& opt) {
+  const int want = opt.max_streams == 0 ? kDefaultLanes : opt.max_streams;
+  L.lanes = std::max(1, std::min<int>(want, (int)L.groups.size()));
+  std::vector<std::pair<double, int>> order;
+  std::vector<double> load(L.lanes, 0.0);
+  L.lane_of_group.assign(L.groups.size(), 0);
+  L.late_group = -1;
+  std::vector<long long> fewest_of(L.groups.size(), 0);
+  std::vector<int> row;
+  bool any_big = false;
+  for (size_t gi = 0; gi < L.groups.size(); ++gi) {
+    const Group& g = L.groups[gi];
+    long long fewest = -1;
+    for (int kind = OP_GRAM; kind <= OP_APPLY; ++kind) {
+      const long long t = launch_tiles(g, kind, pick_tile(g, kind, (int)g.members.size()), (int)g.members.size());
+      if (fewest < 0 || t < fewest) fewest = t;
+    }
+    fewest_of[gi] = fewest;
+    any_big = any_big || fewest >= kBigLaunchTiles;
+  }
+  std::vector<double> work_of(L.groups.size(), 0.0);
+  for (size_t gi = 0; gi < L.groups.size(); ++gi) {
+    const Group& g = L.groups[gi];
+    const double p = std::min(g.rows_pad, g.cols_pad), q = std::max(g.rows_pad, g.cols_pad);
+    // flop of five iterations on the symmetric count: literal 5 (3 p^2 q + p^3), fused chunks (3, 2)
+    const double per = g.fused ? 6.0 * p * p * q + 14.0 * p * p * p : 5.0 * (3.0 * p * p * q + p * p * p);
+    const double work = per * (double)g.members.size();
+    work_of[gi] = work;
+    // Beside a group that keeps the caller's stream, only groups too small to fill the chip by
+    // themselves go to the side streams (their launch latency hides behind the large group); a
+    // mid-sized group there gained 0.3 % at most (4 squares of 4096 beside 384 experts), and in a row
+    // the per-launch times of a profile add up to the phase time.
+    const bool in_row = fewest_of[gi] >= kBigLaunchTiles || (any_big && fewest_of[gi] >= kChipTiles);
+    if (in_row) { load[0] += work; row.push_back((int)gi); }
+    else order.emplace_back(-work, (int)gi);
+  }
+  std::sort(order.begin(), order.end());
+  for (auto& pr : order) {
+    const int lane = (int)(std::min_element(load.begin(), load.end()) - load.begin());
+    L.lane_of_group[pr.second] = lane;
+    load[lane] += -pr.first;
+  }
+  // The groups on the lanes run side by side.  When their launches, taken together, put a large tile
+  // on at least half of the CUs, each of them uses the large-tile kernel even where its own launch
+  // alone would be too small for it (measured on one dense block of hidden size 2048: 2.43 against
+  // 2.80 ms per step).
+  if (L.lanes > 1) {
+    long long together = 0;
+    for (auto& pr : order) {
+      Group& g = L.groups[pr.second];
+      if (g.f32 || g.gran < 256) continue;
+      long long fewest = -1;
+      for (int kind = OP_GRAM; kind <= OP_APPLY; ++kind) {
+        const long long t = launch_tiles(g, kind, TileShape{256, 256}, (int)g.members.size());
+        if (fewest < 0 || t < fewest) fewest = t;
+      }
+      together += fewest;
+    }
+    if (together >= 128)
+      for (auto& pr : order) L.groups[pr.second].large_with_company = true;
+  }
+  if (opt.overlap == MONA_OVERLAP_LATE_GROUP && row.size() >= 2 && !L.external_state) {
+    int late = -1;
+    double most = 0.0, others = 0.0;
+    auto elems = [&](int gi) { return (double)L.groups[gi].m * L.groups[gi].n * (double)L.groups[gi].members.size(); };
+    for (int gi : row)
+      if (elems(gi) > most) { most = elems(gi); late = gi; }
+    for (int gi : row)
+      if (gi != late) others += work_of[gi];
+    const double slow_pass = 30.0 * most / kSlowPassBytesPerSec;
+    if (kProductSlowdown * others / kProductFlopPerSec >= 0.95 * slow_pass && slow_pass >= 1.0e-3) L.late_group = late;
+  }
 }
 
 void build_layout(const mona_matrix* mats, int count, const mona_options& opt, bool external_state, Layout& L) {
@@ -212,19 +347,27 @@ void build_layout(const mona_matrix* mats, int count, const mona_options& opt, b
   }
   L.work_bytes = off - L.work_begin;
 
+  plan_lanes(L, opt);
+
   // elementwise work table
   L.first_block.assign(count, 0);
   L.num_blocks.assign(count, 0);
-  for (int pass = 0; pass < 2; ++pass) {
+  for (int pass = 0; pass < 4; ++pass) {
     for (int i = 0; i < count; ++i) {
-      if ((mats[i].g_dtype == MONA_BF16) != (pass == 1)) continue;
+      if ((mats[i].g_dtype == MONA_BF16) != ((pass & 1) == 1)) continue;
+      if ((L.group_of[i] == L.late_group) != (pass >= 2)) continue;
       const int64_t ne = (int64_t)mats[i].m * mats[i].n;
       const int nb = (int)((ne + kEwChunk - 1) / kEwChunk);
       L.first_block[i] = (int)L.blocks.size();
       L.num_blocks[i] = nb;
       for (int c = 0; c < nb; ++c) L.blocks.push_back(BlockWork{i, c});
     }
-    if (pass == 0) L.blocks_f32g = (int)L.blocks.size();
+    L.range_end[pass] = (int)L.blocks.size();
+  }
+  for (int late = 0; late < 2; ++late) {
+    for (int i = 0; i < count; ++i)
+      if ((L.group_of[i] == L.late_group) == (late == 1)) L.order.push_back(i);
+    if (late == 0) L.num_early = (int)L.order.size();
   }
 
   // tables
@@ -232,20 +375,12 @@ void build_layout(const mona_matrix* mats, int count, const mona_options& opt, b
   L.dyn_off = off;      off = align_up(off + sizeof(MatDynamic) * count);
   L.scales_off = off;   off = align_up(off + sizeof(MatScale) * count);
   L.optr_off = off;     off = align_up(off + sizeof(void*) * count);
+  L.order_off = off;    off = align_up(off + sizeof(int32_t) * count);
   L.partials_off = off; off = align_up(off + sizeof(double) * L.blocks.size());
   L.blocks_off = off;   off = align_up(off + sizeof(BlockWork) * L.blocks.size());
   for (Group& g : L.groups) { g.members_off = off; off = align_up(off + sizeof(int32_t) * g.members.size()); }
   L.total = off;
 }
-
-constexpr int kRing = 4;
-constexpr int kProfSets = 32;
-constexpr int kDefaultLanes = 4;   // streams the shape groups of one step are spread over
-// launches of at least this many tiles keep 256 CUs busy for six rounds or more.  Measured: with the limit at
-// 512 or 768 mid-sized groups (a bank of 64 experts of 1024 x 2048) lose 4 % by waiting for each other; at
-// 3072 the two expert groups of a 128-expert layer run side by side and lose 5 % to each other's L2 traffic.
-constexpr long long kBigLaunchTiles = 1536;
-constexpr long long kChipTiles = 256;      // one tile per CU
 
 struct LaunchRecord {
   int kind, group, iter, tile;
@@ -268,7 +403,10 @@ struct mona_state {
   std::vector<hipStream_t> side;       // lanes 1..
   std::vector<hipEvent_t> side_done;   // one per side stream
   hipEvent_t fork_ev = nullptr;
-  std::vector<int> lane_of_group;      // group index -> lane
+  // the late group's elementwise pass: a stream confined to a quarter of the CUs
+  hipStream_t late_stream = nullptr;
+  hipEvent_t late_fork = nullptr, late_done = nullptr;
+  int late_cus = 0;                    // CUs that stream may use (0: no such stream)
   // pinned ring for the per-step pointer table
   MatDynamic* ring[kRing] = {nullptr, nullptr, nullptr, nullptr};
   hipEvent_t ring_ev[kRing];
@@ -293,30 +431,6 @@ struct mona_state {
 };
 
 namespace {
-
-struct TileShape { int bm, bn; };
-
-// block tile used by one product of a group
-TileShape pick_tile(const Group& g, int kind, int count) {
-  if (g.f32 || g.gran < 256) return {128, 128};
-  long long tiles;
-  if (kind == OP_APPLY) {
-    tiles = (long long)(g.rows_pad / 256) * (g.cols_pad / 256) * count;
-  } else {
-    const long long t = g.p_pad / 256;
-    tiles = t * (t + 1) / 2 * count;
-  }
-  // too few large tiles to fill 256 CUs, unless groups running beside this one make up for it
-  if (tiles < 192 && !g.large_with_company) return {128, 128};
-  return {256, 256};
-}
-
-// tiles one product launch of a group computes
-long long launch_tiles(const Group& g, int kind, TileShape tile, int count) {
-  if (kind == OP_APPLY) return (long long)(g.rows_pad / tile.bm) * (g.cols_pad / tile.bn) * count;
-  const long long t = g.p_pad / tile.bm;
-  return t * (t + 1) / 2 * count;
-}
 
 double gemm_flops(const GemmArgs& a) {
   return 2.0 * a.tile_m * a.tile_n * (double)a.K * a.tiles_per_mat * a.count;
@@ -642,6 +756,9 @@ int mona_init_state(const mona_matrix* mats, int32_t count, const mona_options* 
     for (hipStream_t q : st->side) (void)hipStreamDestroy(q);
     for (hipEvent_t e : st->side_done) (void)hipEventDestroy(e);
     if (st->fork_ev) (void)hipEventDestroy(st->fork_ev);
+    if (st->late_stream) (void)hipStreamDestroy(st->late_stream);
+    if (st->late_fork) (void)hipEventDestroy(st->late_fork);
+    if (st->late_done) (void)hipEventDestroy(st->late_done);
     delete st;
     return code;
   };
@@ -667,72 +784,26 @@ int mona_init_state(const mona_matrix* mats, int32_t count, const mona_options* 
   st->ev_valid = true;             // from here on cleanup() destroys the events created so far
   for (auto& set : st->ev) for (auto& e : set) INIT_TRY(hipEventCreate(&e));
   {
-    // Lanes.  A group whose every launch covers the chip many times over gains nothing from company
-    // (two persistent kernels sharing the CUs only disturb each other's L2 reuse: measured slower), so
-    // such groups stay in a row on the caller's stream; the others, sorted by work, each go to the
-    // least loaded lane.
-    const int want = o.max_streams == 0 ? kDefaultLanes : o.max_streams;
-    const int lanes = std::max(1, std::min<int>(want, (int)L.groups.size()));
-    std::vector<std::pair<double, int>> order;
-    std::vector<double> load(lanes, 0.0);
-    st->lane_of_group.assign(L.groups.size(), 0);
-    std::vector<long long> fewest_of(L.groups.size(), 0);
-    bool any_big = false;
-    for (size_t gi = 0; gi < L.groups.size(); ++gi) {
-      const Group& g = L.groups[gi];
-      long long fewest = -1;
-      for (int kind = OP_GRAM; kind <= OP_APPLY; ++kind) {
-        const long long t = launch_tiles(g, kind, pick_tile(g, kind, (int)g.members.size()), (int)g.members.size());
-        if (fewest < 0 || t < fewest) fewest = t;
-      }
-      fewest_of[gi] = fewest;
-      any_big = any_big || fewest >= kBigLaunchTiles;
-    }
-    for (size_t gi = 0; gi < L.groups.size(); ++gi) {
-      const Group& g = L.groups[gi];
-      const double p = std::min(g.rows_pad, g.cols_pad), q = std::max(g.rows_pad, g.cols_pad);
-      const double work = (3.0 * p * p * q + p * p * p) * (double)g.members.size();
-      // Beside a group that keeps the caller's stream, only groups too small to fill the chip by
-      // themselves go to the side streams (their launch latency hides behind the large group); a
-      // mid-sized group there gained 0.3 % at most (4 squares of 4096 beside 384 experts), and in a row
-      // the per-launch times of a profile add up to the phase time.
-      const bool in_row = fewest_of[gi] >= kBigLaunchTiles || (any_big && fewest_of[gi] >= kChipTiles);
-      if (in_row) load[0] += work;
-      else order.emplace_back(-work, (int)gi);
-    }
-    std::sort(order.begin(), order.end());
-    for (auto& pr : order) {
-      const int lane = (int)(std::min_element(load.begin(), load.end()) - load.begin());
-      st->lane_of_group[pr.second] = lane;
-      load[lane] += -pr.first;
-    }
-    // The groups on the lanes run side by side.  When their launches, taken together, put a large tile
-    // on at least half of the CUs, each of them uses the large-tile kernel even where its own launch
-    // alone would be too small for it (measured on one dense block of hidden size 2048: 2.43 against
-    // 2.80 ms per step).
-    if (lanes > 1) {
-      long long together = 0;
-      for (auto& pr : order) {
-        Group& g = st->L.groups[pr.second];
-        if (g.f32 || g.gran < 256) continue;
-        long long fewest = -1;
-        for (int kind = OP_GRAM; kind <= OP_APPLY; ++kind) {
-          const long long t = launch_tiles(g, kind, TileShape{256, 256}, (int)g.members.size());
-          if (fewest < 0 || t < fewest) fewest = t;
-        }
-        together += fewest;
-      }
-      if (together >= 128)
-        for (auto& pr : order) st->L.groups[pr.second].large_with_company = true;
-    }
     INIT_TRY(hipEventCreateWithFlags(&st->fork_ev, hipEventDisableTiming));
-    for (int i = 1; i < lanes; ++i) {
+    for (int i = 1; i < L.lanes; ++i) {
       hipStream_t side = nullptr;
       INIT_TRY(hipStreamCreateWithFlags(&side, hipStreamNonBlocking));
       st->side.push_back(side);
       hipEvent_t done = nullptr;
       INIT_TRY(hipEventCreateWithFlags(&done, hipEventDisableTiming));
       st->side_done.push_back(done);
+    }
+    if (L.late_group >= 0) {
+      // a stream that may use the first quarter of the CUs only (the mask's bits are dealt to the dies in
+      // turn, so every die gives up the same number); default priority
+      const int cus = device_cu_count();
+      const int share = cus / kOverlapCuShare;
+      std::vector<uint32_t> mask((cus + 31) / 32, 0u);
+      for (int i = 0; i < share; ++i) mask[i / 32] |= 1u << (i % 32);
+      INIT_TRY(hipExtStreamCreateWithCUMask(&st->late_stream, (uint32_t)mask.size(), mask.data()));
+      INIT_TRY(hipEventCreateWithFlags(&st->late_fork, hipEventDisableTiming));
+      INIT_TRY(hipEventCreateWithFlags(&st->late_done, hipEventDisableTiming));
+      st->late_cus = share;
     }
   }
 
@@ -749,6 +820,8 @@ int mona_init_state(const mona_matrix* mats, int32_t count, const mona_options* 
   INIT_TRY(hipMemcpyAsync(st->arena + L.stat_off, stat.data(), sizeof(MatStatic) * count, hipMemcpyHostToDevice, s));
   INIT_TRY(hipMemcpyAsync(st->arena + L.optr_off, optr.data(), sizeof(void*) * count, hipMemcpyHostToDevice, s));
   INIT_TRY(hipMemcpyAsync(st->arena + L.blocks_off, L.blocks.data(), sizeof(BlockWork) * L.blocks.size(),
+                          hipMemcpyHostToDevice, s));
+  INIT_TRY(hipMemcpyAsync(st->arena + L.order_off, L.order.data(), sizeof(int32_t) * L.order.size(),
                           hipMemcpyHostToDevice, s));
   for (const Group& g : L.groups) {
     std::vector<int32_t> mem(g.members.begin(), g.members.end());
@@ -810,8 +883,12 @@ int enqueue_step(mona_state* st, const mona_hparams* hp, hipStream_t s) {
 
   // A HIP call that fails once kernels of the step are in flight leaves the state arrays half updated:
   // join whatever was forked, mark the state unusable and say so.
-  bool forked = false;
+  bool forked = false, late_forked = false;
   auto bail = [&](hipError_t e, const char* what) {
+    if (late_forked) {
+      (void)hipEventRecord(st->late_done, st->late_stream);
+      (void)hipStreamWaitEvent(s, st->late_done, 0);
+    }
     if (forked)
       for (size_t i = 0; i < st->side.size(); ++i) {
         (void)hipEventRecord(st->side_done[i], st->side[i]);
@@ -834,21 +911,49 @@ int enqueue_step(mona_state* st, const mona_hparams* hp, hipStream_t s) {
   st->pool_used = 0;
   if (prof) STEP_TRY(hipEventRecord(ev[0], s));
 
-  // Alg. 1: difference, acceleration EMA, accelerated gradient, momentum, roll; sum of squares
+  // Alg. 1: difference, acceleration EMA, accelerated gradient, momentum, roll; sum of squares.
+  // With a late group its pass goes to the stream that owns a quarter of the CUs and runs beside the
+  // products of the other groups (not while every launch is timed on its own, and not under stream
+  // capture, where the CU mask of a stream would not survive into the graph anyway).
   const bool muon_only = (hp->flags & MONA_FLAG_MUON_ONLY) != 0;
   const int use_prev = muon_only ? 2 : !((hp->flags & MONA_FLAG_FIRST_DIFF_ZERO) && st->k == 0);
   const int sbf = st->opt.state_dtype == MONA_BF16;
   const int one = L.one_buffer ? 1 : 0;
-  STEP_TRY(launch_state_update(stat, dyn, blocks, partials, L.blocks_f32g, 0, sbf, one, hp->momentum, hp->beta_a,
-                               hp->alpha, use_prev, s));
-  STEP_TRY(launch_state_update(stat, dyn, blocks + L.blocks_f32g, partials + L.blocks_f32g, nblocks - L.blocks_f32g,
-                               1, sbf, one, hp->momentum, hp->beta_a, hp->alpha, use_prev, s));
+  const int T = hp->ns_steps;
+  // (nor on the null stream: a stream with a CU mask can only be created as a blocking one, and the null
+  // stream waits for every blocking stream, which would put the two passes in a row again)
+  bool overlap = st->late_stream != nullptr && st->profiling < 2 && T > 0 && s != nullptr;
+  if (overlap) {
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    STEP_TRY(hipStreamIsCapturing(s, &cap));
+    overlap = cap == hipStreamCaptureStatusNone;
+  }
+  const int32_t* order = st->at<int32_t>(L.order_off);
+  auto pass = [&](int r0, int r1, int g_bf16, hipStream_t q) {
+    return launch_state_update(stat, dyn, blocks + r0, partials + r0, r1 - r0, g_bf16, sbf, one, hp->momentum,
+                               hp->beta_a, hp->alpha, use_prev, q);
+  };
+  if (overlap) {
+    STEP_TRY(hipEventRecord(st->late_fork, s));
+    late_forked = true;
+    STEP_TRY(hipStreamWaitEvent(st->late_stream, st->late_fork, 0));
+    STEP_TRY(pass(L.range_end[1], L.range_end[2], 0, st->late_stream));
+    STEP_TRY(pass(L.range_end[2], L.range_end[3], 1, st->late_stream));
+    STEP_TRY(launch_norm_finalize(stat, partials, scales, order + L.num_early, count - L.num_early, hp->ns_eps,
+                                  st->late_stream));
+    STEP_TRY(hipEventRecord(st->late_done, st->late_stream));
+  }
+  STEP_TRY(pass(0, L.range_end[0], 0, s));
+  STEP_TRY(pass(L.range_end[0], L.range_end[1], 1, s));
+  if (!overlap) {
+    STEP_TRY(pass(L.range_end[1], L.range_end[2], 0, s));
+    STEP_TRY(pass(L.range_end[2], L.range_end[3], 1, s));
+  }
   if (L.one_buffer && !muon_only) st->last_beta_a = hp->beta_a;
-  STEP_TRY(launch_norm_finalize(stat, partials, scales, count, hp->ns_eps, s));
+  STEP_TRY(launch_norm_finalize(stat, partials, scales, order, overlap ? L.num_early : count, hp->ns_eps, s));
   if (prof) STEP_TRY(hipEventRecord(ev[1], s));
 
   // Newton-Schulz (Eq. newton_schulz), T iterations per shape group
-  const int T = hp->ns_steps;
   st->fused_update = T > 0;
   // per-launch timing serialises the launches on the caller's stream so that each interval is one kernel
   const bool fork = !st->side.empty() && st->profiling < 2 && T > 0;
@@ -858,10 +963,21 @@ int enqueue_step(mona_state* st, const mona_hparams* hp, hipStream_t s) {
     for (hipStream_t q : st->side) STEP_TRY(hipStreamWaitEvent(q, st->fork_ev, 0));
   }
   std::vector<Op> ops;
-  for (size_t gi = 0; gi < L.groups.size(); ++gi) {
+  const int ngroups = (int)L.groups.size();
+  for (int pos = 0; pos < ngroups; ++pos) {
+    // the late group comes last: its elementwise pass must have finished, and from then on the chip is free
+    int gi = pos;
+    if (L.late_group >= 0) gi = pos == ngroups - 1 ? L.late_group : (pos < L.late_group ? pos : pos + 1);
     Group& g = L.groups[gi];
-    const int lane = fork ? st->lane_of_group[gi] : 0;
+    const int lane = fork ? L.lane_of_group[gi] : 0;
     hipStream_t gs = lane == 0 ? s : st->side[lane - 1];
+    int cu_cap = 0;
+    if (overlap && gi == L.late_group) {
+      STEP_TRY(hipStreamWaitEvent(s, st->late_done, 0));
+      late_forked = false;
+    } else if (overlap) {
+      cu_cap = device_cu_count() - st->late_cus;
+    }
     ops.clear();
     g.o_buf = OpBuilder(st, g, *hp, ops).build();
     for (const Op& op : ops) {
@@ -871,10 +987,10 @@ int enqueue_step(mona_state* st, const mona_hparams* hp, hipStream_t s) {
         if (!get_event_pair(st, &rec.e0, &rec.e1)) return bail(hipErrorOutOfMemory, "hipEventCreate");
         STEP_TRY(hipEventRecord(rec.e0, gs));
       }
-      STEP_TRY(launch_ns_gemm(op.a, op.tile.bm, op.tp, op.tq, g.f32, gs));
+      STEP_TRY(launch_ns_gemm(op.a, op.tile.bm, op.tp, op.tq, g.f32, cu_cap, gs));
       if (each) {
         STEP_TRY(hipEventRecord(rec.e1, gs));
-        rec.kind = op.kind; rec.group = (int)gi; rec.iter = op.iter; rec.tile = op.tile.bm * 1000 + op.tile.bn;
+        rec.kind = op.kind; rec.group = gi; rec.iter = op.iter; rec.tile = op.tile.bm * 1000 + op.tile.bn;
         rec.flops = gemm_flops(op.a);
         st->records.push_back(rec);
       }
@@ -1028,7 +1144,6 @@ int mona_step_noalloc(const mona_matrix* mat, const mona_options* opts, void* g_
   st.mats.assign(mat, mat + 1);
   st.arena = base;
   st.k = k;
-  st.lane_of_group.assign(L.groups.size(), 0);
   hipStream_t s = static_cast<hipStream_t>(stream);
   // The array keeps what the last call left in it: the padding of the working matrices and the scales must
   // start from zero (a fill kernel, not a memset: the call may be under graph capture).
@@ -1041,7 +1156,8 @@ int mona_step_noalloc(const mona_matrix* mat, const mona_options* opts, void* g_
   md.w = mat->w; md.g = mat->g; md.slot = nullptr;
   HIP_TRY(launch_single_tables(ms, md, o_ptr, st.at<MatStatic>(L.stat_off), st.at<MatDynamic>(L.dyn_off),
                                st.at<void*>(L.optr_off), st.at<BlockWork>(L.blocks_off), (int)L.blocks.size(),
-                               reinterpret_cast<int32_t*>(base + L.groups[0].members_off), s));
+                               reinterpret_cast<int32_t*>(base + L.groups[0].members_off),
+                               st.at<int32_t>(L.order_off), s));
   rc = enqueue_step(&st, hp, s);
   if (rc) return rc;
   note_unstable_alpha(hp);
@@ -1066,6 +1182,9 @@ int mona_free_state(mona_state* st) {
   for (hipStream_t q : st->side) { (void)hipStreamSynchronize(q); (void)hipStreamDestroy(q); }
   for (hipEvent_t e : st->side_done) (void)hipEventDestroy(e);
   if (st->fork_ev) (void)hipEventDestroy(st->fork_ev);
+  if (st->late_stream) { (void)hipStreamSynchronize(st->late_stream); (void)hipStreamDestroy(st->late_stream); }
+  if (st->late_fork) (void)hipEventDestroy(st->late_fork);
+  if (st->late_done) (void)hipEventDestroy(st->late_done);
   delete st;
   return MONA_OK;
 }

@@ -91,17 +91,20 @@ hipError_t launch_state_update(const MatStatic* stat, const MatDynamic* dyn, con
                                double* partials, int num_blocks, int g_bf16, int state_bf16, int one_buffer,
                                float mu, float beta_a, float alpha, int use_prev, hipStream_t s);
 // norm_finalize_kernel, then rescue_kernel (repairs the working copies of flagged matrices)
+// `list` (DEVICE, may be NULL = matrices 0 .. count - 1): the matrix indices to finalise
 hipError_t launch_norm_finalize(const MatStatic* stat, const double* partials, MatScale* scales,
-                                int count, float eps, hipStream_t s);
+                                const int32_t* list, int count, float eps, hipStream_t s);
 // tables of a one-matrix state written by a kernel from its arguments (no host copy)
 hipError_t launch_single_tables(const MatStatic& ms, const MatDynamic& md, void* o_ptr, MatStatic* stat,
                                 MatDynamic* dyn, void** o_ptrs, BlockWork* work, int num_blocks, int32_t* members,
-                                hipStream_t s);
+                                int32_t* order, hipStream_t s);
 hipError_t launch_plain_update(const MatStatic* stat, const MatDynamic* dyn, const MatScale* scales,
                                const BlockWork* work, int num_blocks, void* const* o_ptrs, float lr, float wd,
                                float gamma_coeff, int store_o, hipStream_t s);
-hipError_t launch_ns_gemm(const GemmArgs& a, int tile, bool transP, bool transQ, bool f32,
+// cu_cap > 0: the persistent large-tile kernel uses at most that many CUs (the rest are busy elsewhere)
+hipError_t launch_ns_gemm(const GemmArgs& a, int tile, bool transP, bool transQ, bool f32, int cu_cap,
                           hipStream_t s);
+int device_cu_count();
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 
 }  // namespace mona

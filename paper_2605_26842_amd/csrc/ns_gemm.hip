@@ -1191,7 +1191,17 @@ hipError_t launch_bf16(const GemmArgs& a, bool tp, bool tq, int grid, hipStream_
 
 }  // namespace
 
-hipError_t launch_ns_gemm(const GemmArgs& a, int tile, bool transP, bool transQ, bool f32, hipStream_t s) {
+int device_cu_count() {
+  static const int num_cus = []() {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < kXcds)
+      n = 256;
+    return n / kXcds * kXcds;
+  }();
+  return num_cus;
+}
+
+hipError_t launch_ns_gemm(const GemmArgs& a, int tile, bool transP, bool transQ, bool f32, int cu_cap, hipStream_t s) {
   const long long total = (long long)a.tiles_per_mat * a.count;
   if (total <= 0) return hipSuccess;
   if (total > 0x7fffff00LL) return hipErrorInvalidValue;
@@ -1206,13 +1216,11 @@ hipError_t launch_ns_gemm(const GemmArgs& a, int tile, bool transP, bool transQ,
   }
   if (tile == 256 && a.tile_n == 256) {
     // persistent: one workgroup per CU walks its share of the tiles
-    static const int num_cus = []() {
-      int dev = 0, n = 0;
-      if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < kXcds)
-        n = 256;
-      return n / kXcds * kXcds;
-    }();
-    const int pgrid = grid < num_cus ? grid : num_cus;
+    static const int num_cus = device_cu_count();
+    // (cu_cap: the caller keeps some CUs for a kernel that runs beside this one; every workgroup of a
+    // persistent launch must be resident at once or the tile walk falls into two rounds)
+    const int cap = (cu_cap >= kXcds && cu_cap < num_cus) ? cu_cap / kXcds * kXcds : num_cus;
+    const int pgrid = grid < cap ? grid : cap;
 #define MONA_LAUNCH_DMA(TP_, TQ_, UPD_, E_)                                                                        \
   hipLaunchKernelGGL((ns_gemm_bf16_dma_kernel<256, 256, 2, 4, 4, 1, TP_, TQ_, UPD_, E_, false>), dim3(pgrid), dim3(512), 0, s, a)
     const bool upd = a.epilogue == EPI_UPDATE, has_e = a.E != nullptr;

@@ -191,8 +191,9 @@ constexpr double kNormLo = 9.094947017729282e-13;   // 2^-40
 constexpr double kNormHi = 1099511627776.0;         // 2^40
 __global__ __launch_bounds__(64) void norm_finalize_kernel(const MatStatic* __restrict__ stat,
                                                            const double* __restrict__ partials,
-                                                           MatScale* __restrict__ scales, float eps) {
-  const int mat = blockIdx.x;
+                                                           MatScale* __restrict__ scales,
+                                                           const int32_t* __restrict__ list, float eps) {
+  const int mat = list ? list[blockIdx.x] : blockIdx.x;
   const int first = stat[mat].first_block, nb = stat[mat].num_blocks;
   double s = 0.0;
   for (int i = threadIdx.x; i < nb; i += 64) s += partials[first + i];
@@ -231,11 +232,13 @@ __global__ __launch_bounds__(64) void norm_finalize_kernel(const MatStatic* __re
 // matrix whose norm lies outside the safe window gets the copy M 2^e.  Every block scans the flags and
 // leaves at once when none is set.
 __global__ __launch_bounds__(256) void rescue_kernel(const MatStatic* __restrict__ stat,
-                                                     const MatScale* __restrict__ scales, int count) {
+                                                     const MatScale* __restrict__ scales,
+                                                     const int32_t* __restrict__ list, int count) {
   int any = 0;
-  for (int i = threadIdx.x; i < count; i += 256) any |= (scales[i].status & 6u) != 0;
+  for (int i = threadIdx.x; i < count; i += 256) any |= (scales[list ? list[i] : i].status & 6u) != 0;
   if (!__syncthreads_or(any)) return;
-  for (int mat = 0; mat < count; ++mat) {
+  for (int li = 0; li < count; ++li) {
+    const int mat = list ? list[li] : li;
     const uint32_t st = scales[mat].status;
     if (!(st & 6u)) continue;
     const MatStatic ms = stat[mat];
@@ -255,9 +258,9 @@ __global__ __launch_bounds__(256) void rescue_kernel(const MatStatic* __restrict
 // point that may neither allocate nor copy from host memory).
 __global__ __launch_bounds__(256) void single_tables_kernel(MatStatic ms, MatDynamic md, void* o_ptr, MatStatic* stat,
                                                             MatDynamic* dyn, void** o_ptrs, BlockWork* work,
-                                                            int num_blocks, int32_t* members) {
+                                                            int num_blocks, int32_t* members, int32_t* order) {
   const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i == 0) { stat[0] = ms; dyn[0] = md; o_ptrs[0] = o_ptr; members[0] = 0; }
+  if (i == 0) { stat[0] = ms; dyn[0] = md; o_ptrs[0] = o_ptr; members[0] = 0; order[0] = 0; }
   for (int b = i; b < num_blocks; b += gridDim.x * 256) work[b] = BlockWork{0, b};
 }
 
@@ -345,22 +348,22 @@ hipError_t launch_state_update(const MatStatic* stat, const MatDynamic* dyn, con
   return launch_su_mode<MODE_TWO_BUFFER>(stat, dyn, work, partials, num_blocks, g_bf16, state_bf16, c, s);
 }
 
-hipError_t launch_norm_finalize(const MatStatic* stat, const double* partials, MatScale* scales, int count,
-                                float eps, hipStream_t s) {
+hipError_t launch_norm_finalize(const MatStatic* stat, const double* partials, MatScale* scales,
+                                const int32_t* list, int count, float eps, hipStream_t s) {
   if (count <= 0) return hipSuccess;
-  hipLaunchKernelGGL(norm_finalize_kernel, dim3(count), dim3(64), 0, s, stat, partials, scales, eps);
+  hipLaunchKernelGGL(norm_finalize_kernel, dim3(count), dim3(64), 0, s, stat, partials, scales, list, eps);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(rescue_kernel, dim3(1024), dim3(256), 0, s, stat, scales, count);
+  hipLaunchKernelGGL(rescue_kernel, dim3(1024), dim3(256), 0, s, stat, scales, list, count);
   return hipGetLastError();
 }
 
 hipError_t launch_single_tables(const MatStatic& ms, const MatDynamic& md, void* o_ptr, MatStatic* stat,
                                 MatDynamic* dyn, void** o_ptrs, BlockWork* work, int num_blocks, int32_t* members,
-                                hipStream_t s) {
+                                int32_t* order, hipStream_t s) {
   const int blocks = num_blocks > 256 * 64 ? 64 : (num_blocks + 255) / 256;
   hipLaunchKernelGGL(single_tables_kernel, dim3(blocks > 0 ? blocks : 1), dim3(256), 0, s, ms, md, o_ptr, stat, dyn,
-                     o_ptrs, work, num_blocks, members);
+                     o_ptrs, work, num_blocks, members, order);
   return hipGetLastError();
 }
 

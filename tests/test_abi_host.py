@@ -135,7 +135,7 @@ def test_bad_arguments_are_rejected_on_the_host():
     rc, msg = rc_of(lib.mona_state_size, shapes((4, 4)), 1, C.byref(B.mona_options(0, 0, 3)), C.byref(out))
     assert rc == B.MONA_EINVAL and "accel_form" in msg
     rc, msg = rc_of(lib.mona_state_size, shapes((4, 4)), 1,
-                    C.byref(B.mona_options(0, 0, 0, 0, 0, (C.c_int32 * 3)(0, 1, 0))), C.byref(out))
+                    C.byref(B.mona_options(0, 0, 0, 0, 0, 0, (C.c_int32 * 2)(0, 1))), C.byref(out))
     assert rc == B.MONA_EINVAL and "reserved" in msg
     rc, msg = rc_of(lib.mona_state_size, shapes((4, 4)), 1, C.byref(B.mona_options(0, 0, 0, 9)), C.byref(out))
     assert rc == B.MONA_EINVAL and "max_streams" in msg

@@ -70,3 +70,39 @@ def test_fused_schedule_on_ill_conditioned_momentum():
         errs[schedule] = H.rel_fro(hist[0][5].O, ref["O"])
     say("[ill-conditioned] O rel Fro err: literal %.3e, fused %.3e" % (errs[1], errs[2]))
     assert errs[2] <= 2.0 * errs[1] + 1e-2
+
+
+def test_late_group_overlap_changes_timing_not_results():
+    """mona_options.overlap = MONA_OVERLAP_LATE_GROUP: the elementwise pass of the group with the most elements
+    runs on a CU-masked stream beside the products of the other group.  Same kernels on the same data, so
+    every output must be bit-identical to the run without it; and the pass must really have left the common
+    elementwise phase (its share of the step's first interval is gone)."""
+    say("[case] late-group overlap")
+    dev = "cuda:0"
+    shapes = [(1024, 1024)] * 200 + [(512, 1536)] * 400
+    run_stream = torch.cuda.Stream(dev)          # not the null stream: it would serialise the two passes
+    results = {}
+    with torch.cuda.stream(run_stream):
+        grads = [[wl.GradientStream(s, 3500 + i, dev).next() for i, s in enumerate(shapes)] for _ in range(2)]
+        for mode in (B.MONA_OVERLAP_OFF, B.MONA_OVERLAP_LATE_GROUP):
+            weights = [wl.draw_weight(s, 3400 + i, torch.bfloat16, dev) for i, s in enumerate(shapes)]
+            opt = B.MonaOptimizer(weights, overlap=mode)
+            opt.set_profiling(1)
+            hp = wl.HParams()
+            first = []
+            for gs in grads + grads:
+                opt.step(gs, hp)
+                first.append(opt.last_step_times()[0])
+            run_stream.synchronize()
+            results[mode] = (weights, [opt.momentum(i).clone() for i in (0, 199, 200, 599)],
+                             [opt.accel(i).clone() for i in (0, 199, 200, 599)], min(first[1:]), opt.status())
+            del opt
+    w0, m0, a0, t0, s0 = results[B.MONA_OVERLAP_OFF]
+    w1, m1, a1, t1, s1 = results[B.MONA_OVERLAP_LATE_GROUP]
+    say(f"[late-group overlap] elementwise interval before the products: {t0:.3f} ms without, {t1:.3f} ms with")
+    assert s0 == s1 == [0] * len(shapes)
+    for i in range(len(shapes)):
+        assert torch.equal(w0[i], w1[i]), f"matrix {i}: parameters differ with the late-group overlap"
+    for x, y in zip(m0 + a0, m1 + a1):
+        assert torch.equal(x, y)
+    assert t1 < 0.8 * t0

@@ -28,7 +28,7 @@ def run_pair(shape, seed, steps, w_dtype, state_dtype, hp):
     g_prev = torch.zeros(shape, dtype=state_dtype, device=dev)
     acc = torch.zeros(shape, dtype=state_dtype, device=dev)
     mom = torch.zeros(shape, dtype=torch.float32, device=dev)
-    opts = B.mona_options(0, B._dtype_code(state_dtype), B.MONA_ACCEL_TWO_BUFFER, 0, 0, (C.c_int32 * 3)())
+    opts = B.mona_options(0, B._dtype_code(state_dtype), B.MONA_ACCEL_TWO_BUFFER, 0, 0, 0, (C.c_int32 * 2)())
     hpc = B.make_hparams(hp)
     s = torch.cuda.current_stream().cuda_stream
     for k, g in enumerate(grads):
@@ -63,7 +63,7 @@ def test_noalloc_rejects_what_does_not_fit():
         B.mona_step_noalloc(B.make_matrices([w], [g]), None, st.data_ptr(), st.data_ptr(), st.data_ptr(),
                             B.make_hparams(wl.HParams()), 0, 0)
     assert ei.value.code == B.MONA_ENOMEM and "static scratch" in str(ei.value)
-    opts = B.mona_options(0, 0, B.MONA_ACCEL_ONE_BUFFER, 0, 0, (C.c_int32 * 3)())
+    opts = B.mona_options(0, 0, B.MONA_ACCEL_ONE_BUFFER, 0, 0, 0, (C.c_int32 * 2)())
     small = torch.zeros((64, 64), dtype=torch.float32, device=dev)
     with pytest.raises(B.MonaError) as ei:
         B.mona_step_noalloc(B.make_matrices([small], [small]), opts, small.data_ptr(), small.data_ptr(),
