@@ -153,6 +153,10 @@ WORKLOADS = {
         "paper_moe_6b",
         (MatrixSpec("expert.up", 1536, 1024, 128), MatrixSpec("expert.down", 1024, 1536, 128)),
         torch.bfloat16, 5, "MOE-6B-A0d5B expert shapes"),
+    "paper_moe_68b": Workload(
+        "paper_moe_68b",
+        (MatrixSpec("expert.up", 3072, 1024, 256), MatrixSpec("expert.down", 1024, 3072, 256)),
+        torch.bfloat16, 5, "MOE-68B-A3B expert shapes (one layer: hidden 3072, 256 experts of FFN size 1024)"),
 }
 
 # order of BASELINE configs

@@ -106,3 +106,23 @@ def test_late_group_overlap_changes_timing_not_results():
     for x, y in zip(m0 + a0, m1 + a1):
         assert torch.equal(x, y)
     assert t1 < 0.8 * t0
+
+
+def test_the_papers_own_expert_shapes():
+    """One matrix of each expert shape of the paper's three models (Sec. 6 model descriptions: hidden 768 with FFN
+    256, hidden 1536 with FFN 1024, hidden 3072 with FFN 1024), tall and wide, in groups large enough for the
+    large-tile kernel, three steps, against the oracle."""
+    say("[case] the paper's expert shapes")
+    dev = "cuda:0"
+    base = [(768, 256), (256, 768), (1536, 1024), (1024, 1536), (3072, 1024), (1024, 3072)]
+    shapes = [s for s in base for _ in range(16)]
+    sample = [16 * j + (5 * j) % 16 for j in range(len(base))]
+    weights = [wl.draw_weight(s, 3600 + i, torch.bfloat16, dev) for i, s in enumerate(shapes)]
+    streams = [wl.GradientStream(s, 3700 + i, dev) for i, s in enumerate(shapes)]
+    grads = [[st.next() for st in streams] for _ in range(3)]
+    hp = wl.HParams(beta_a=0.98, alpha=-25.0)           # the pair reported for the 6B model
+    w_cpu = [x.cpu() if i in sample else x for i, x in enumerate(weights)]
+    opt, _, hist = H.run_gpu(weights, grads, hp, 0, watch=sample)
+    worst = H.check_history(w_cpu, grads, hp, hist, sample, H.TOL_NS_BF16, label="paper shapes")
+    say("[worst]", worst)
+    assert opt.status() == [0] * len(shapes)

@@ -48,3 +48,19 @@ def test_make_inputs_layout():
     assert [tuple(x.shape) for x in w] == shapes
     assert len(g) == 2 and [tuple(x.shape) for x in g[1]] == shapes
     assert not torch.equal(g[0][0], g[1][0])
+
+
+def test_in_place_gradient_stream():
+    """`advance` overwrites the previous gradient: same draws as `next`, same AR(1) recurrence up to the
+    order of rounding."""
+    shape = (64, 96)
+    a, b = wl.GradientStream(shape, 11), wl.GradientStream(shape, 11)
+    g = torch.empty(shape)
+    for k in range(4):
+        want = a.next()
+        b.advance(g)
+        assert torch.allclose(g, want, rtol=1e-5, atol=1e-9)
+        if k == 0:
+            assert torch.equal(g, want)
+    paper = wl.WORKLOADS["paper_moe_68b"]
+    assert len(paper.shapes()) == 512 and paper.shapes()[0] == (3072, 1024) and paper.shapes()[-1] == (1024, 3072)
