@@ -83,6 +83,12 @@ def cpu_baseline(workload, hp, budget_s: float = 30.0):
     }
 
 
+def n_elem_bytes_w(workload) -> int:
+    """Bytes of all parameters of the workload."""
+    import torch
+    return workload.num_elements() * (2 if workload.w_dtype == torch.bfloat16 else 4)
+
+
 def bench_adamw(args) -> int:
     """The AdamW step of the non-matrix parameters (its own JSON line; not part of the headline metric)."""
     import numpy as np
@@ -284,9 +290,21 @@ def main() -> int:
         opt.step(ring[k % len(ring)], hpc, slots)
         k += 1
     (ew_serial_ms, ns_serial_ms, _, step_serial_ms), _ = opt.mean_step_times()
-    launches = None
+    launches = opt.last_step_launches()
+    # Step (c), the parameter update: it rides in the epilogue of each group's last apply launch.  Its HBM
+    # traffic is W read + W written; its cost is what those launches take beyond an apply of the same group
+    # that carries no update.
+    fused_upd_ms = plain_ms = 0.0
+    groups_seen = set()
+    for r in launches:
+        if r["kind"] == 2 and r["iter"] == hp.ns_steps - 1:
+            others = [q["ms"] for q in launches if q["kind"] == 2 and q["group"] == r["group"] and q["iter"] != r["iter"]]
+            if others:
+                fused_upd_ms += r["ms"]
+                plain_ms += sum(others) / len(others)
+                groups_seen.add(r["group"])
+    w_bytes = 2 * n_elem_bytes_w(workload)
     if args.per_launch:
-        launches = opt.last_step_launches()
         kinds = {0: "gram", 1: "poly", 2: "apply", 3: "sym"}
         for r in launches:
             tf = r["flops"] / (r["ms"] * 1e-3) / 1e12 if r["ms"] > 0 else 0.0
@@ -351,6 +369,8 @@ def main() -> int:
             "ms_per_step": ns_ms,
             "avg_launch_ms": ns_ms / max(plan["ns_launches"], 1),
             "ms_per_step_phases_in_a_row": ns_serial_ms,
+            "elementwise": {"bound": "hbm", "achieved": ew_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                            "frac": ew_gbs / PEAK_HBM_GBS},
         },
         "elementwise": {
             "kernel": "state_update + norm_finalize", "bound": "hbm", "achieved": ew_gbs, "peak": PEAK_HBM_GBS,
@@ -358,6 +378,17 @@ def main() -> int:
             "traffic": traffic_ew,
             "measured": "3 steps after the timed ones with the phases one after the other on the launch stream "
                         "(in the timed steps part of this pass may run beside the products on a quarter of the CUs)",
+        },
+        "update": {
+            "kernel": "last apply launch of every shape group (Eq. muon_update fused into its epilogue)",
+            "bound": "hbm", "bytes_per_step": w_bytes,
+            "ms_update_launches": fused_upd_ms, "ms_same_launches_without_update": plain_ms,
+            "ms_added_by_update": fused_upd_ms - plain_ms,
+            "achieved_over_the_launches": w_bytes / (fused_upd_ms * 1e-3) / 1e9 if fused_upd_ms > 0 else None,
+            "achieved_over_the_added_time": w_bytes / ((fused_upd_ms - plain_ms) * 1e-3) / 1e9 if fused_upd_ms > plain_ms else None,
+            "peak": PEAK_HBM_GBS, "unit": "GB/s",
+            "note": "the launches are bound by the matrix units; the parameter traffic hides behind their products, "
+                    "so over the added time alone it can exceed the HBM peak",
         },
         "phases_ms": {"elementwise_before_products": ew_ms, "newton_schulz": ns_ms, "separate_update": upd_ms,
                       "step_events": step_ms_events, "steps_averaged": n_phase,
