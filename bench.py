@@ -163,6 +163,9 @@ def main() -> int:
     ap.add_argument("--grad-ring", type=int, default=2)
     ap.add_argument("--muon-only", action="store_true",
                     help="plain Muon step (acceleration buffers untouched): the baseline of the paper's overhead figure")
+    ap.add_argument("--zero-gradients", action="store_true",
+                    help="all-zero gradients: the same launches and instruction stream on operands that do not "
+                         "toggle (an experiment on the power limit, not a benchmark)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-launch", action="store_true", help="also print per-launch timings to stderr")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -223,6 +226,10 @@ def main() -> int:
             # gets its own draw
             streams = [wl.GradientStream(s, wl.matrix_seed(widx, i), dev) for i, s in enumerate(shapes)]
         ring.append([st.next().to(g_dtype) for st in streams])
+    if args.zero_gradients:
+        for gs in ring:
+            for g in gs:
+                g.zero_()
     del streams
     accel_form = {"two-buffer": B.MONA_ACCEL_TWO_BUFFER, "one-buffer": B.MONA_ACCEL_ONE_BUFFER,
                   "caller-slot": B.MONA_ACCEL_CALLER_SLOT}[args.accel_form]
@@ -355,7 +362,7 @@ def main() -> int:
             "state_dtype": args.state_dtype, "accel_form": args.accel_form, "ns_steps": hp.ns_steps, "ns_precision": args.ns_precision,
             "grad_ring": len(ring), "optimizer": "muon" if args.muon_only else "mona",
             "launch": "hip graph replay" if graph is not None else "eager", "streams": args.streams,
-            "ns_schedule": args.ns_schedule, "overlap": args.overlap,
+            "ns_schedule": args.ns_schedule, "overlap": args.overlap, "zero_gradients": bool(args.zero_gradients),
         },
         "roofline": {
             "kernel": "ns_gemm (grouped Newton-Schulz products, %d launches/step)" % plan["ns_launches"],
