@@ -172,9 +172,10 @@ def main() -> int:
                     help="also run one plain 1 GiB elementwise copy (negation; a reference kernel of known traffic for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--ns-steps", type=int, default=5, help="Newton-Schulz iterations T (the paper's 5)")
-    ap.add_argument("--ns-schedule", default="auto", choices=["auto", "literal", "fused"],
+    ap.add_argument("--ns-schedule", default="auto", choices=["auto", "literal", "fused", "pairs"],
                     help="layout of the Newton-Schulz iterations as products: literal = Gram, poly, apply per "
-                         "iteration; fused = chunks of iterations advanced on the p x p side; auto = the library's choice")
+                         "iteration; fused = chunks of three then two iterations advanced on the p x p side; pairs = chunks of "
+                         "two; auto = the library's choice per shape group")
     ap.add_argument("--overlap", default="off", choices=["off", "late-group"],
                     help="late-group: the elementwise pass of the largest shape group runs beside the products of the "
                          "other groups on a quarter of the CUs; off (the library's default): one elementwise pass "
@@ -238,7 +239,7 @@ def main() -> int:
         slots = [torch.zeros(s, dtype=state_dtype, device=dev) for s in shapes]
     opt = B.MonaOptimizer(weights, ns_precision=args.ns_precision, state_dtype=state_dtype, g_dtype=g_dtype,
                           accel_form=accel_form, max_streams=args.streams,
-                          ns_schedule={"auto": 0, "literal": 1, "fused": 2}[args.ns_schedule],
+                          ns_schedule={"auto": 0, "literal": 1, "fused": 2, "pairs": 3}[args.ns_schedule],
                           overlap={"off": 0, "late-group": 1}[args.overlap])
     hpc = B.make_hparams(hp)
     plan = opt.plan_info(hp.ns_steps)

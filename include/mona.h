@@ -113,10 +113,12 @@ typedef struct mona_options {
                              Q_t = a I + b S_t + c S_t^2 an iteration is X_{t+1} = Q_t X_t and S_{t+1} = S_t Q_t^2,
                              so a chunk forms S once, advances it on the p x p side and applies the product of its
                              Q_t to X once: fewer flop whenever the long side exceeds the short one;
-                           MONA_NS_SCHEDULE_AUTO (0): fused for bf16 groups whose long side q is at least 1.5
-                             times the short side p and for which 1 / sqrt(p) + 1 / sqrt(q) <= 0.0438 (e.g.
-                             1536 x 4096, 2048 x 8192: there the fused form measured as accurate as the literal
-                             one or better), literal otherwise                                          */
+                           MONA_NS_SCHEDULE_PAIRS (3): the same in chunks of two;
+                           MONA_NS_SCHEDULE_AUTO (0): per shape group, for bf16 groups whose long side q is at
+                             least 1.5 times the short side p: chunks of three then two where
+                             1 / sqrt(p) + 1 / sqrt(q) <= 0.0438 (e.g. 1536 x 4096, 2048 x 8192: there the fused
+                             form measured as accurate as the literal one or better), chunks of two where the
+                             padded short side is at least 1024 (e.g. 1024 x 2048), literal otherwise    */
   int32_t overlap;      /* MONA_OVERLAP_OFF (0): one elementwise pass over every matrix, then the products.
                            MONA_OVERLAP_LATE_GROUP (1): when several large shape groups run one after the
                            other, the elementwise pass (HBM-bound) of the one with the most elements runs on a
@@ -138,6 +140,7 @@ typedef struct mona_options {
 #define MONA_NS_SCHEDULE_AUTO 0
 #define MONA_NS_SCHEDULE_LITERAL 1
 #define MONA_NS_SCHEDULE_FUSED 2
+#define MONA_NS_SCHEDULE_PAIRS 3
 
 #define MONA_ACCEL_TWO_BUFFER 0
 #define MONA_ACCEL_ONE_BUFFER 1

@@ -23,7 +23,7 @@ MONA_FLAG_FIRST_DIFF_ZERO, MONA_FLAG_KEEP_O, MONA_FLAG_MUON_ONLY = 0x1, 0x2, 0x4
 MONA_VIEW_G_PREV, MONA_VIEW_A, MONA_VIEW_M, MONA_VIEW_NORM, MONA_VIEW_O, MONA_VIEW_C = 0, 1, 2, 3, 4, 5
 MONA_ACCEL_TWO_BUFFER, MONA_ACCEL_ONE_BUFFER, MONA_ACCEL_CALLER_SLOT = 0, 1, 2
 MONA_STATUS_ZERO_NORM, MONA_STATUS_NONFINITE, MONA_STATUS_RESCALED = 0x1, 0x2, 0x4
-MONA_NS_SCHEDULE_AUTO, MONA_NS_SCHEDULE_LITERAL, MONA_NS_SCHEDULE_FUSED = 0, 1, 2
+MONA_NS_SCHEDULE_AUTO, MONA_NS_SCHEDULE_LITERAL, MONA_NS_SCHEDULE_FUSED, MONA_NS_SCHEDULE_PAIRS = 0, 1, 2, 3
 MONA_OVERLAP_OFF, MONA_OVERLAP_LATE_GROUP = 0, 1
 
 EXPORTED = (

@@ -49,7 +49,8 @@ int fail(int code, const char* fmt, ...) {
 
 constexpr size_t kAlign = 256;
 constexpr int kSmallSideF32 = 64;
-constexpr double kFusedMaxStart = 0.0438;  // largest 1 / sqrt(p) + 1 / sqrt(q) for which the automatic choice fuses iterations
+constexpr double kFusedMaxStart = 0.0438;  // largest 1 / sqrt(p) + 1 / sqrt(q) for which the automatic choice fuses three iterations
+constexpr int kPairsMinShortSide = 1024;   // padded short side from which it fuses pairs of iterations otherwise
 size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a; }
 int round_up(int v, int a) { return (v + a - 1) / a * a; }
 
@@ -65,7 +66,8 @@ struct Group {
   bool large_with_company = false;  // 256 x 256 tiles even for launches of few tiles (set when the state is built)
   int esize = 2;             // bytes per element of this group's working copies
   std::vector<int> members;  // matrix indices
-  bool fused = false;        // Newton-Schulz iterations taken in chunks on the p x p side (see build_ops)
+  int fused = 0;             // Newton-Schulz iterations taken in chunks on the p x p side (see OpBuilder):
+                             // 0 literal, 1 chunks of two, 2 a chunk of three and then chunks of two
   int npp = 2;               // p x p working matrices: S and B (literal schedule) or S, S', U, Q, R, R' (fused)
   int o_buf = 1;             // which ping-pong buffer holds O_k of the last step
   size_t x_off[2] = {0, 0};  // byte offsets in the arena: ping-pong X buffers
@@ -132,8 +134,8 @@ int check_opts(const mona_options* o, mona_options* out) {
     return fail(MONA_EINVAL, "accel_form must be MONA_ACCEL_TWO_BUFFER, MONA_ACCEL_ONE_BUFFER or MONA_ACCEL_CALLER_SLOT");
   if (z.max_streams < 0 || z.max_streams > 8) return fail(MONA_EINVAL, "max_streams must lie in [0, 8]");
   if (z.ns_schedule != MONA_NS_SCHEDULE_AUTO && z.ns_schedule != MONA_NS_SCHEDULE_LITERAL &&
-      z.ns_schedule != MONA_NS_SCHEDULE_FUSED)
-    return fail(MONA_EINVAL, "ns_schedule must be MONA_NS_SCHEDULE_AUTO, _LITERAL or _FUSED");
+      z.ns_schedule != MONA_NS_SCHEDULE_FUSED && z.ns_schedule != MONA_NS_SCHEDULE_PAIRS)
+    return fail(MONA_EINVAL, "ns_schedule must be MONA_NS_SCHEDULE_AUTO, _LITERAL, _FUSED or _PAIRS");
   if (z.overlap != MONA_OVERLAP_OFF && z.overlap != MONA_OVERLAP_LATE_GROUP)
     return fail(MONA_EINVAL, "overlap must be MONA_OVERLAP_OFF or MONA_OVERLAP_LATE_GROUP");
   for (int r : z.reserved)
@@ -218,8 +220,9 @@ void plan_lanes(Layout& L, const mona_options& opt) {
   for (size_t gi = 0; gi < L.groups.size(); ++gi) {
     const Group& g = L.groups[gi];
     const double p = std::min(g.rows_pad, g.cols_pad), q = std::max(g.rows_pad, g.cols_pad);
-    // flop of five iterations on the symmetric count: literal 5 (3 p^2 q + p^3), fused chunks (3, 2)
-    const double per = g.fused ? 6.0 * p * p * q + 14.0 * p * p * p : 5.0 * (3.0 * p * p * q + p * p * p);
+    // flop of five iterations on the symmetric count: literal 5 (3 p^2 q + p^3), chunks (3, 2), chunks (2, 2, 1)
+    const double per = g.fused == 2 ? 6.0 * p * p * q + 14.0 * p * p * p
+                       : g.fused == 1 ? 9.0 * p * p * q + 11.0 * p * p * p : 5.0 * (3.0 * p * p * q + p * p * p);
     const double work = per * (double)g.members.size();
     work_of[gi] = work;
     // Beside a group that keeps the caller's stream, only groups too small to fill the chip by
@@ -319,15 +322,20 @@ void build_layout(const mona_matrix* mats, int count, const mona_options& opt, b
       // it from X while its eigenvalues are still small (the growth phase of the iteration) and less so
       // once they have reached the band around 1.  A full-rank matrix of this shape starts from singular
       // values up to about 1 / sqrt(p) + 1 / sqrt(q) and each early iteration multiplies them by a = 3.4445,
-      // so the automatic choice fuses (the first chunk is three iterations) only where a^2 times that bound
-      // is still around one half.  Measured against the float64 oracle on the benchmark's inputs: 1536 x 4096
-      // 7.1e-3 fused against 9.1e-3 literal, 2048 x 8192 6.8e-3 against 9.7e-3; but 1024 x 2048 1.5e-2
-      // against 9.5e-3 and 512 x 4096 1.6e-2 against 1.3e-2, which therefore stay literal.
+      // so the automatic choice fuses three iterations only where a^2 times that bound is still around one
+      // half, and otherwise pairs of iterations, down to a short side of 1024.  Measured O error against the
+      // float64 oracle on the benchmark's inputs, (3, 2) / (2, 2, 1) / literal: 1536 x 4096 7.1e-3 / 1.07e-2 /
+      // 9.1e-3, 2048 x 8192 6.8e-3 / 1.07e-2 / 9.7e-3; 1024 x 2048 1.5e-2 / 1.2e-2 / 9.5e-3, 1024 x 4096
+      // 1.4e-2 / 9.5e-3 / 9.1e-3; 512 x 4096 1.6e-2 / 1.3e-2 / 1.3e-2 (too small to gain: literal).
       const double q_pad = g.tall ? g.rows_pad : g.cols_pad;
       const double start = 1.0 / std::sqrt((double)g.p_pad) + 1.0 / std::sqrt(q_pad);
-      g.fused = !g.f32 && (opt.ns_schedule == MONA_NS_SCHEDULE_FUSED ||
-                           (opt.ns_schedule == MONA_NS_SCHEDULE_AUTO && 2.0 * q_pad >= 3.0 * g.p_pad &&
-                            start <= kFusedMaxStart));
+      g.fused = 0;
+      if (!g.f32) {
+        if (opt.ns_schedule == MONA_NS_SCHEDULE_FUSED) g.fused = 2;
+        else if (opt.ns_schedule == MONA_NS_SCHEDULE_PAIRS) g.fused = 1;
+        else if (opt.ns_schedule == MONA_NS_SCHEDULE_AUTO && 2.0 * q_pad >= 3.0 * g.p_pad)
+          g.fused = start <= kFusedMaxStart ? 2 : (g.p_pad >= kPairsMinShortSide ? 1 : 0);
+      }
       g.npp = g.fused ? 6 : 2;
       L.groups.push_back(g);
     } else {
@@ -445,14 +453,14 @@ struct Op {
   bool tp = false, tq = false;
 };
 
-// Newton-Schulz iterations per chunk.  Literal schedule: one.  Fused schedule: three, then twos (measured
-// on bf16-rounded products: fusing the late iterations, or more than three of them, loses accuracy on
-// ill-conditioned inputs; three early ones and pairs afterwards do not).
-std::vector<int> chunk_sizes(int T, bool fused) {
+// Newton-Schulz iterations per chunk.  Literal schedule: one.  Fused schedules: three and then twos, or twos
+// only (measured on bf16-rounded products: fusing the late iterations, or more than three of them, loses
+// accuracy; three early ones and pairs afterwards do not).
+std::vector<int> chunk_sizes(int T, int fused) {
   std::vector<int> out;
   if (!fused) { out.assign(T, 1); return out; }
   int left = T;
-  if (left >= 3) { out.push_back(3); left -= 3; }
+  if (fused == 2 && left >= 3) { out.push_back(3); left -= 3; }
   while (left >= 2) { out.push_back(2); left -= 2; }
   if (left) out.push_back(1);
   return out;

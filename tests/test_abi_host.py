@@ -70,14 +70,15 @@ def test_state_size_accounts_for_state_and_workspace():
     assert total - literal == 384 * 4 * 1536 * 1536 * 2
     fused = B.mona_state_size(layer, 388, B.mona_options(ns_schedule=B.MONA_NS_SCHEDULE_FUSED))
     assert fused - total == 4 * 4 * 4096 * 4096 * 2
-    # the automatic choice leaves 1024 x 2048 and 512 x 4096 literal and fuses 2048 x 8192
-    for shape, is_fused in (((1024, 2048), False), ((512, 4096), False), ((2048, 8192), True), ((8192, 2048), True),
-                            ((1536, 1536), False)):
+    # the automatic choice fuses 2048 x 8192 (chunks of three, then two) and 1024 x 2048 (pairs) and leaves
+    # 512 x 4096 (short side too small to gain) and squares literal
+    for shape, is_fused in (((1024, 2048), True), ((512, 4096), False), ((2048, 8192), True), ((8192, 2048), True),
+                            ((1536, 1536), False), ((768, 256), False)):
         auto = B.mona_state_size(shapes(shape), 1)
         lit = B.mona_state_size(shapes(shape), 1, B.mona_options(ns_schedule=B.MONA_NS_SCHEDULE_LITERAL))
         assert (auto > lit) == is_fused, shape
     with pytest.raises(B.MonaError):
-        B.mona_state_size(layer, 388, B.mona_options(ns_schedule=3))
+        B.mona_state_size(layer, 388, B.mona_options(ns_schedule=4))
 
 
 def rc_of(fn, *args):
