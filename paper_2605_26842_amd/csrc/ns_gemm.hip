@@ -374,10 +374,12 @@ struct Epilogue {
         wave_sync();
         constexpr int RCH = 32 / CH;               // row-chunks per band
         constexpr int MPASSES = WN * RCH / 64;
+        constexpr int RPI = 64 / RCH;              // rows of the mirrored tile one store touches: all RCH pieces
+                                                   // of a row go out together (stores that touch fewer rows
+                                                   // are cheaper)
 #pragma unroll
         for (int pss = 0; pss < MPASSES; ++pss) {
-          const int idx = pss * 64 + lane;
-          const int c = idx % WN, rc = idx / WN;
+          const int c = pss * RPI + lane % RPI, rc = lane / RPI;
           vec_t ov;
 #pragma unroll
           for (int e = 0; e < CH; ++e) ov[e] = (T)stage[(rc * CH + e) * LDW + c];
@@ -389,19 +391,20 @@ struct Epilogue {
 };
 
 #define MONA_AS3_EPI __attribute__((address_space(3)))
-// Eight transposed LDS reads (4 rows x 16 columns of bf16 per group of 16 lanes and read), 1024 bytes =
-// 4 staged rows apart, then one wait.  A free function: an asm statement cannot name variables captured
-// by a lambda.  The destination registers are written when the data returns and stay untouched until
-// the wait, which is tied to them.
-__device__ __forceinline__ void tr_read_32_rows(u32x2 (&lo)[4], u32x2 (&hi)[4], uint32_t addr) {
+// Eight transposed LDS reads (4 rows x 16 columns of bf16 per group of 16 lanes and read): four column slabs
+// of 16 (32 bytes apart) for rows r0 .. r0 + 3, and the same for rows r0 + 4 .. r0 + 7 (1024 bytes = 4 staged
+// rows further on), then one wait.  A free function: an asm statement cannot name variables captured by a
+// lambda.  The destination registers are written when the data returns and stay untouched until the wait,
+// which is tied to them.
+__device__ __forceinline__ void tr_read_8_rows(u32x2 (&lo)[4], u32x2 (&hi)[4], uint32_t addr) {
   asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo[0]) : "v"(addr));
   asm volatile("ds_read_b64_tr_b16 %0, %1 offset:1024" : "=v"(hi[0]) : "v"(addr));
-  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:2048" : "=v"(lo[1]) : "v"(addr));
-  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:3072" : "=v"(hi[1]) : "v"(addr));
-  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:4096" : "=v"(lo[2]) : "v"(addr));
-  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:5120" : "=v"(hi[2]) : "v"(addr));
-  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:6144" : "=v"(lo[3]) : "v"(addr));
-  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:7168" : "=v"(hi[3]) : "v"(addr));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:32" : "=v"(lo[1]) : "v"(addr));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:1056" : "=v"(hi[1]) : "v"(addr));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:64" : "=v"(lo[2]) : "v"(addr));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:1088" : "=v"(hi[2]) : "v"(addr));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:96" : "=v"(lo[3]) : "v"(addr));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:1120" : "=v"(hi[3]) : "v"(addr));
   asm volatile("s_waitcnt lgkmcnt(0)"
                : "+v"(lo[0]), "+v"(hi[0]), "+v"(lo[1]), "+v"(hi[1]), "+v"(lo[2]), "+v"(hi[2]), "+v"(lo[3]), "+v"(hi[3]));
 }
@@ -415,7 +418,7 @@ __device__ __forceinline__ void tr_read_32_rows(u32x2 (&lo)[4], u32x2 (&hi)[4], 
 // row % 16, which spreads both the column-wise writes and the row-wise reads over all banks).
 // Mirrored (symmetric) tiles: each pass leaves its rounded bf16 row in the 256 bytes of the fp32 row it
 // has just consumed (at 32 (row % 4) bytes inside it), and ds_read_b64_tr_b16 then hands every lane 4
-// consecutive rows of one column: two of them make the 16-byte piece of the transposed tile.
+// consecutive rows of one column: two of them make a 16-byte piece of the transposed tile.
 //
 // Global loads and stores: the load counter of this target counts both and stores retire out of order,
 // so once a store is in flight every wait for a load drains everything, stores included.  The E chunks
@@ -644,19 +647,21 @@ struct BlockEpilogue {
       if (HAS_E && c_acc == 1.0f) passes(IC<1>{}); else passes(IC<0>{});
       if (mirror) {
         // 16 lanes fetch a 4 (rows) x 16 (columns) block of the bf16 rows: lane j of the group points at
-        // row j / 4, columns 4 (j % 4) .. + 3 and receives the 4 rows of column j.  Group g of the
-        // wavefront takes columns 16 g .. 16 g + 15; two reads (rows r0 .. r0 + 3 and r0 + 4 .. r0 + 7,
-        // 4 x 256 bytes further on) give 8 consecutive rows of the lane's column.
+        // row j / 4, columns 4 (j % 4) .. + 3 and receives the 4 rows of column j.  Group g of the wavefront
+        // takes rows 8 g .. 8 g + 7 of the block row (two reads, 4 x 256 bytes apart) and, one after the
+        // other, the four slabs of 16 columns: per store the four groups then write the four 16-byte pieces
+        // of the same 16 rows of the mirrored tile, 64 contiguous bytes per row (measured: stores that touch
+        // 16 rows cost half of stores that touch 64).
         wave_sync();
         const int j16 = lane & 15, g = lane >> 4;
-        const int rr = j16 >> 2;     // + 8 h; (rr + 8 h) % 4 == rr
-        const uint32_t addr = stage_addr + rr * 256 + rr * 32 + (16 * g + 4 * (j16 & 3)) * 2;
+        const int rr = j16 >> 2;     // (8 g + rr + 4) % 4 == rr: the staged row's offset inside its slot
+        const uint32_t addr = stage_addr + (8 * g + rr) * 256 + rr * 32 + (4 * (j16 & 3)) * 2;
         u32x2 lo[4], hi[4];
-        tr_read_32_rows(lo, hi, addr);
-        const int n = 16 * g + j16;
-        static_for<4>([&](auto h) {
-          const u32x4 tv = {lo[h].x, lo[h].y, hi[h].x, hi[h].y};
-          *reinterpret_cast<u32x4*>(Cm + 2u * ((uint32_t)(n * a.ldc) + (uint32_t)(i * 32 + h * 8))) = tv;
+        tr_read_8_rows(lo, hi, addr);
+        static_for<4>([&](auto sl) {
+          const u32x4 tv = {lo[sl].x, lo[sl].y, hi[sl].x, hi[sl].y};
+          const int n = 16 * sl + j16;
+          *reinterpret_cast<u32x4*>(Cm + 2u * ((uint32_t)(n * a.ldc) + (uint32_t)(i * 32 + g * 8))) = tv;
         });
       }
     });
