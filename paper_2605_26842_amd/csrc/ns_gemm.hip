@@ -420,8 +420,8 @@ __device__ __forceinline__ void tr_read_8_rows(u32x2 (&lo)[4], u32x2 (&hi)[4], u
 // has just consumed (at 32 (row % 4) bytes inside it), and ds_read_b64_tr_b16 then hands every lane 4
 // consecutive rows of one column: two of them make a 16-byte piece of the transposed tile.
 //
-// Global loads and stores: the load counter of this target counts both and stores retire out of order,
-// so once a store is in flight every wait for a load drains everything, stores included.  The E chunks
+// Global loads and stores: the load counter of this target counts both, in issue order, so once a store
+// is in flight a wait for a load issued after it waits for the store as well.  The E chunks
 // (and the parameter chunks of the fused update) of a whole batch of NPF passes are therefore requested
 // together, waited for ONCE (settle(), which also tells the compiler that these registers hold plain
 // values from then on), and the stores of the passes then stream without any wait.  HAS_E is a template
@@ -1024,9 +1024,11 @@ __global__ __launch_bounds__(64 * WGM * WGN, MIN_BLOCKS) void ns_gemm_bf16_dma_k
   issue(2, 2);
   for (int round = 0;; ++round) {
     // entry: chunks 0..2 of tile t are in flight (or landed) in stages 0..2; stage 3 is free
-    // Stores of the previous epilogue may still be in flight and, unlike loads, may retire out of
-    // order: counting "all but n" is only safe once they are gone, so drain everything here (the
-    // loads of stages 0..2 were issued a whole epilogue ago).
+    // Stores of the previous epilogue may still be in flight, and how many depends on the tile (mirrored
+    // or not, with or without the update), so "all but n" cannot be counted from here on until they are
+    // gone: drain everything (the loads of stages 0..2 were issued a whole epilogue ago; a variant that
+    // counted the stores instead measured no faster: the time goes into the barrier below, waiting for
+    // the wavefronts whose epilogue ends later).
     MONA_WAIT_VM(0);
     __builtin_amdgcn_s_barrier();
     issue(3, 3);
